@@ -1,0 +1,169 @@
+"""Plain CPU fp64 oracle of the compressed linear layer.  TEST INFRASTRUCTURE ONLY.
+
+What it computes (spec notation; the paper's is in brackets):
+
+  forward   Y  = X . W                exact output            [Def. 3.1: Z = X W^T]
+            Xs = X^T . S              stored low-rank factor  [Sec. 4: V of X^ = U V^T, with U = S]
+  backward  dX = dY . W^T             exact input gradient    [Def. 3.1: G_X = (grad_Z L) W; Thm 3.2.2(a)]
+            Gr = S^T . dY             small gradient factor   [Sec. 4: ((grad_Z L)^T U)^T]
+            dW = Xs . Gr              factored weight grad    [Sec. 4: G^_W = ((grad_Z L)^T U) V^T, transposed]
+
+S is the n x r random-projection compressor (the paper's "RP" option, Experimental
+Setup) taken along the token axis with i.i.d. N(0, 1/r) entries, so that
+E[S S^T] = I and the reconstructed activation S S^T X is unbiased, the premise of
+Thm 3.2.1(a).  The paper does not define RP's matrix, axis, scaling or random
+number generator; the readings used here are:
+
+  * integers: Philox4x32-10 (Salmon et al., SC'11), key = (seed low word, seed high word),
+    counter = (g >> 2 low word, column j, stream id 0, g >> 34) with g = row_offset + i
+    the global token index; the four output words belong to tokens 4q..4q+3 of column j;
+  * uniform:  u = ((x >> 9) + 0.5) * 2^-23, exactly representable in fp32 and fp64;
+  * normal:   Box-Muller on the word pairs (x0, x1) and (x2, x3):
+              z_even = R cos(theta), z_odd = R sin(theta), R = sqrt(-2 ln u_first),
+              theta = 2 pi u_second;  S[i, j] = z / sqrt(r).
+
+Everything after the integer stream is fp64 and unrounded.  Matrix products are
+numpy's matmul on float64 (a library primitive used as one step); nothing is
+blocked, fused or reordered.  The optional *_rounded helpers round S, Xs and Gr to
+bfloat16 where the GPU path does, to separate quantisation from mistakes.
+
+Pins (tests/test_oracle_*.py): published Philox known answers; Box-Muller polar
+identities and normal moments / KS distance; integer matrices against pure-Python
+loops; exactness with an orthogonal S at r = n; Monte-Carlo unbiasedness
+(Thm 3.2.1(a)); the Gaussian-sketch variance closed form (Thm 3.3.1 per-layer
+term); the 1/sqrt(r) error law matching the paper's RP error table; dX independent
+of seed and rank (Thm 3.2.2(a)).  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+PHILOX_M0 = 0xD2511F53
+PHILOX_M1 = 0xCD9E8D57
+PHILOX_W0 = 0x9E3779B9
+PHILOX_W1 = 0xBB67AE85
+_MASK32 = np.uint64(0xFFFFFFFF)
+
+
+def philox4x32_10(counter, key):
+    """Philox4x32 with 10 rounds (Salmon et al., SC'11).
+
+    counter: uint32 array [..., 4]; key: uint32 array broadcastable to [..., 2].
+    Returns uint32 array [..., 4].
+    """
+    c = np.asarray(counter, dtype=np.uint64)
+    k = np.asarray(key, dtype=np.uint64)
+    c0, c1, c2, c3 = (c[..., t] for t in range(4))
+    k0 = np.broadcast_to(k[..., 0], c0.shape).copy()
+    k1 = np.broadcast_to(k[..., 1], c0.shape).copy()
+    for _ in range(10):
+        p0 = np.uint64(PHILOX_M0) * c0          # 32 x 32 -> 64 bit products
+        p1 = np.uint64(PHILOX_M1) * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & _MASK32
+        hi1, lo1 = p1 >> np.uint64(32), p1 & _MASK32
+        c0, c1, c2, c3 = hi1 ^ c1 ^ k0, lo1, hi0 ^ c3 ^ k1, lo0
+        k0 = (k0 + np.uint64(PHILOX_W0)) & _MASK32
+        k1 = (k1 + np.uint64(PHILOX_W1)) & _MASK32
+    return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
+
+
+def sketch_words(seed: int, row_offset: int, n: int, r: int, stream: int = 0):
+    """The integer stream behind S: uint32 [ceil(n/4), r, 4].
+
+    Entry [q, j, w] is output word w of the Philox call for token group q
+    (global tokens row_offset + 4q .. +3) and sketch column j.
+    """
+    if row_offset % 4:
+        raise ValueError("row_offset must be a multiple of 4")
+    nq = (n + 3) // 4
+    g4 = (np.uint64(row_offset) >> np.uint64(2)) + np.arange(nq, dtype=np.uint64)
+    ctr = np.zeros((nq, r, 4), dtype=np.uint64)
+    ctr[..., 0] = (g4 & _MASK32)[:, None]
+    ctr[..., 1] = np.arange(r, dtype=np.uint64)[None, :]
+    ctr[..., 2] = np.uint64(stream)
+    ctr[..., 3] = (g4 >> np.uint64(32))[:, None]          # (g >> 34) of the token index
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint64)
+    return philox4x32_10(ctr, key)
+
+
+def uniform_from_word(x):
+    """u = ((x >> 9) + 0.5) 2^-23, strictly inside (0, 1)."""
+    x = np.asarray(x, dtype=np.uint32)
+    return ((x >> np.uint32(9)).astype(np.float64) + 0.5) * (2.0 ** -23)
+
+
+def normals_from_words(words):
+    """Box-Muller on word pairs: uint32 [..., 4] -> float64 [..., 4] standard normals."""
+    u = uniform_from_word(words)
+    z = np.empty(u.shape, dtype=np.float64)
+    for a in (0, 2):
+        radius = np.sqrt(-2.0 * np.log(u[..., a]))
+        theta = 2.0 * np.pi * u[..., a + 1]
+        z[..., a] = radius * np.cos(theta)
+        z[..., a + 1] = radius * np.sin(theta)
+    return z
+
+
+def sketch_matrix(seed: int, n: int, r: int, row_offset: int = 0):
+    """S: float64 [n, r], entries N(0, 1/r)."""
+    z = normals_from_words(sketch_words(seed, row_offset, n, r))      # [nq, r, 4]
+    z = np.transpose(z, (0, 2, 1)).reshape(-1, r)[:n]                 # token = 4q + w
+    return z / np.sqrt(float(r))
+
+
+def linear_fwd(X, W, seed: int = 0, r: int = 0, row_offset: int = 0, S=None):
+    """Y = X W (exact), Xs = X^T S (the stored factor)."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    if S is None:
+        S = sketch_matrix(seed, X.shape[0], r, row_offset)
+    Y = np.matmul(X, W)
+    Xs = np.matmul(X.T, S)
+    return Y, Xs
+
+
+def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None,
+               want_dW: bool = True):
+    """dX = dY W^T (exact), Gr = S^T dY, dW = Xs Gr (optional)."""
+    dY = np.asarray(dY, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    Xs = np.asarray(Xs, dtype=np.float64)
+    if S is None:
+        S = sketch_matrix(seed, dY.shape[0], r, row_offset)
+    dX = np.matmul(dY, W.T)
+    Gr = np.matmul(S.T, dY)
+    dW = np.matmul(Xs, Gr) if want_dW else None
+    return dX, Gr, dW
+
+
+def reconstruct_activation(Xs, seed: int, n: int, r: int, row_offset: int = 0, S=None):
+    """X^ = U V^T = S Xs^T (Def. 3.1), only used by the invariants."""
+    if S is None:
+        S = sketch_matrix(seed, n, r, row_offset)
+    return np.matmul(S, np.asarray(Xs, dtype=np.float64).T)
+
+
+def round_to_bf16(a):
+    """Round-to-nearest-even to bfloat16, returned as float64 (diagnostic mode only)."""
+    f = np.asarray(a, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.uint64)
+    bits = (bits + np.uint64(0x7FFF) + ((bits >> np.uint64(16)) & np.uint64(1))) & np.uint64(0xFFFF0000)
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64).reshape(f.shape)
+
+
+def linear_fwd_rounded(X, W, seed: int, r: int, row_offset: int = 0):
+    """Diagnostic: as linear_fwd, with S and Xs rounded to bf16 where the bf16 GPU path rounds."""
+    S = round_to_bf16(sketch_matrix(seed, np.asarray(X).shape[0], r, row_offset))
+    Y, Xs = linear_fwd(X, W, S=S)
+    return round_to_bf16(Y), round_to_bf16(Xs)
+
+
+def closed_form_variance(X, dY, r: int):
+    """E||Xs Gr - X^T dY||_F^2 for a Gaussian sketch: (||X||^2 ||dY||^2 + ||X^T dY||^2) / r.
+
+    This is the per-layer compression term of Thm 3.3.1 evaluated for the RP compressor.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    dY = np.asarray(dY, dtype=np.float64)
+    G = np.matmul(X.T, dY)
+    return (np.sum(X * X) * np.sum(dY * dY) + np.sum(G * G)) / float(r)

@@ -1,0 +1,121 @@
+"""Pins for the oracle's layer algebra against definitions, brute force and special cases."""
+import numpy as np
+
+from oracle import acc_oracle as orc
+
+
+def _loops_matmul(A, B):
+    """Definition of a matrix product with Python integers (exact)."""
+    m, k = len(A), len(A[0])
+    n = len(B[0])
+    return [[sum(int(A[i][t]) * int(B[t][j]) for t in range(k)) for j in range(n)] for i in range(m)]
+
+
+def _ints(rng, shape, lo=-5, hi=6):
+    return rng.integers(lo, hi, size=shape).astype(np.int64)
+
+
+def test_forward_backward_against_integer_loops():
+    """Small integer matrices of four different sizes: every operand order/transposition is exercised."""
+    rng = np.random.default_rng(0)
+    n, d_in, d_out, r = 7, 5, 6, 3
+    X, W, dY, S = _ints(rng, (n, d_in)), _ints(rng, (d_in, d_out)), _ints(rng, (n, d_out)), _ints(rng, (n, r))
+    Y, Xs = orc.linear_fwd(X, W, S=S.astype(np.float64))
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=S.astype(np.float64))
+    assert Y.shape == (n, d_out) and Xs.shape == (d_in, r)
+    assert dX.shape == (n, d_in) and Gr.shape == (r, d_out) and dW.shape == (d_in, d_out)
+    assert np.array_equal(Y, np.array(_loops_matmul(X.tolist(), W.tolist()), dtype=np.float64))
+    assert np.array_equal(Xs, np.array(_loops_matmul(X.T.tolist(), S.tolist()), dtype=np.float64))
+    assert np.array_equal(dX, np.array(_loops_matmul(dY.tolist(), W.T.tolist()), dtype=np.float64))
+    assert np.array_equal(Gr, np.array(_loops_matmul(S.T.tolist(), dY.tolist()), dtype=np.float64))
+    want_dW = _loops_matmul(_loops_matmul(X.T.tolist(), S.tolist()), _loops_matmul(S.T.tolist(), dY.tolist()))
+    assert np.array_equal(dW, np.array(want_dW, dtype=np.float64))
+
+
+def test_identity_special_cases():
+    rng = np.random.default_rng(1)
+    n, d_in, d_out = 6, 6, 4
+    W = rng.standard_normal((d_in, d_out))
+    dY = rng.standard_normal((n, d_out))
+    X = rng.standard_normal((n, d_in))
+    Y, _ = orc.linear_fwd(np.eye(n), W, S=np.eye(n))
+    assert np.array_equal(Y, W)                                   # X = I  ->  Y = W
+    _, Xs = orc.linear_fwd(X, W, S=np.eye(n))
+    assert np.array_equal(Xs, X.T)                                # S = I  ->  Xs = X^T
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=np.eye(n))
+    assert np.array_equal(Gr, dY)                                 # S = I  ->  Gr = dY
+    assert np.allclose(dW, X.T @ dY, rtol=1e-13)                  # and dW is the dense gradient
+    # a single non-zero in dY picks one row of W^T
+    e = np.zeros((n, d_out)); e[2, 3] = 2.0
+    dX1, _, _ = orc.linear_bwd(e, W, Xs, S=np.eye(n), want_dW=False)
+    assert np.array_equal(dX1[2], 2.0 * W[:, 3]) and not dX1[[0, 1, 3, 4, 5]].any()
+
+
+def test_exact_with_orthogonal_sketch_at_full_rank():
+    """With r = n and S orthogonal, S S^T = I: the factored gradient is the dense one."""
+    rng = np.random.default_rng(2)
+    n, d_in, d_out = 64, 24, 40
+    X, W, dY = rng.standard_normal((n, d_in)), rng.standard_normal((d_in, d_out)), rng.standard_normal((n, d_out))
+    Q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    _, Xs = orc.linear_fwd(X, W, S=Q)
+    _, _, dW = orc.linear_bwd(dY, W, Xs, S=Q)
+    dense = X.T @ dY
+    assert np.linalg.norm(dW - dense) / np.linalg.norm(dense) < 1e-13
+    assert np.allclose(orc.reconstruct_activation(Xs, 0, n, n, S=Q), X, atol=1e-12)
+
+
+def test_factorisation_adds_no_error_and_rank_bound():
+    """Xs Gr equals (S S^T X)^T dY formed the long way (paper Sec. 4), and has rank <= r."""
+    rng = np.random.default_rng(3)
+    n, d_in, d_out, r, seed = 96, 40, 56, 8, 11
+    X, W, dY = rng.standard_normal((n, d_in)), rng.standard_normal((d_in, d_out)), rng.standard_normal((n, d_out))
+    _, Xs = orc.linear_fwd(X, W, seed, r)
+    _, Gr, dW = orc.linear_bwd(dY, W, Xs, seed, r)
+    Xhat = orc.reconstruct_activation(Xs, seed, n, r)
+    long_way = Xhat.T @ dY
+    assert np.linalg.norm(dW - long_way) / np.linalg.norm(long_way) < 1e-13
+    sv = np.linalg.svd(dW, compute_uv=False)
+    assert sv[r - 1] > 1e-6 * sv[0] and sv[r] < 1e-12 * sv[0]
+    # rank(G_W) <= rank(X): a rank-2 activation gives a rank-2 dense gradient
+    X2 = rng.standard_normal((n, 2)) @ rng.standard_normal((2, d_in))
+    sv2 = np.linalg.svd(X2.T @ dY, compute_uv=False)
+    assert sv2[2] < 1e-12 * sv2[0]
+
+
+def test_input_gradient_is_exact_and_independent_of_compression():
+    """Thm 3.2.2(a): dX does not depend on seed, rank or the stored factor."""
+    rng = np.random.default_rng(4)
+    n, d_in, d_out = 32, 12, 20
+    W, dY = rng.standard_normal((d_in, d_out)), rng.standard_normal((n, d_out))
+    ref = None
+    for seed, r in [(0, 4), (1, 4), (5, 16), (9, 32)]:
+        Xs = rng.standard_normal((d_in, r))
+        dX, _, _ = orc.linear_bwd(dY, W, Xs, seed, r)
+        ref = dX if ref is None else ref
+        assert np.array_equal(dX, ref)
+    assert np.allclose(ref, np.einsum("no,io->ni", dY, W), rtol=1e-13)
+
+
+def test_row_offset_makes_shards_add_up():
+    """Token shards with global row offsets sum to the unsharded factors (data-parallel reading)."""
+    rng = np.random.default_rng(5)
+    n, d_in, d_out, r, seed = 48, 10, 14, 8, 3
+    X, W, dY = rng.standard_normal((n, d_in)), rng.standard_normal((d_in, d_out)), rng.standard_normal((n, d_out))
+    _, Xs = orc.linear_fwd(X, W, seed, r)
+    _, Xs_a = orc.linear_fwd(X[:20], W, seed, r, row_offset=0)
+    _, Xs_b = orc.linear_fwd(X[20:], W, seed, r, row_offset=20)
+    assert np.allclose(Xs_a + Xs_b, Xs, atol=1e-13)
+    _, Gr, _ = orc.linear_bwd(dY, W, Xs, seed, r)
+    _, Gr_a, _ = orc.linear_bwd(dY[:20], W, Xs, seed, r, row_offset=0)
+    _, Gr_b, _ = orc.linear_bwd(dY[20:], W, Xs, seed, r, row_offset=20)
+    assert np.allclose(Gr_a + Gr_b, Gr, atol=1e-13)
+
+
+def test_bf16_rounding_helper():
+    vals = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -2.5, 3.0e38, 1e-40], dtype=np.float64)
+    got = orc.round_to_bf16(vals)
+    assert got[0] == 1.0
+    assert got[1] == 1.0                       # tie -> even mantissa
+    assert got[2] == 1.0 + 2.0 ** -6           # tie -> even mantissa (rounds up)
+    assert got[3] == -2.5
+    assert np.all(np.abs(got[:4] - vals[:4]) <= 2.0 ** -8 * np.abs(vals[:4]))
