@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the compressed linear layer on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input: forward
+(Y = X.W, Xs = X^T.S) and backward (dX = dY.W^T, Gr = S^T.dY, dense dW = Xs.Gr), S regenerated
+from the Philox seed in both.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line (metric: algorithmic TFLOP/s of fwd+bwd; S generation counts zero flops).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2", help="c1 | c2 | c3_r256 | c4 | c5 (a named linear: c4.k)")
+    ap.add_argument("--no-dw", action="store_true", help="leave the dense dW out of the step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--buffer-sets", type=int, default=3, help="rotated so no tensor stays in the 256 MB cache")
+    ap.add_argument("--all-linears", action="store_true", help="also print a per-linear table to stderr")
+    return ap.parse_args()
+
+
+class Buffers:
+    """Device tensors of one linear layer (one rotation slot)."""
+
+    def __init__(self, acc, torch, lin, data, dev, with_dw):
+        code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
+        tdt = acc.torch_dtype(code)
+        self.X, self.W, self.dY = (acc.to_device(data[k], dev) for k in ("X", "W", "dY"))
+        self.Y = torch.empty(lin.n, lin.d_out, dtype=tdt, device=dev)
+        self.dX = torch.empty(lin.n, lin.d_in, dtype=tdt, device=dev)
+        self.Xs = torch.empty(lin.d_in, lin.r, dtype=tdt, device=dev)
+        self.Gr = torch.empty(lin.r, lin.d_out, dtype=tdt, device=dev)
+        self.dW = torch.empty(lin.d_in, lin.d_out, dtype=tdt, device=dev) if with_dw else None
+
+
+def time_events(torch, fn, iters):
+    """Average milliseconds of fn() over iters calls, HIP events on the launch stream."""
+    st = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for i in range(iters):
+        fn(i)
+    e1.record(st)
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(lin, data, with_dw, budget_tokens):
+    """The oracle, as it stands, timed on a bounded token sample of the same workload."""
+    import numpy as np
+    from oracle import acc_oracle as orc
+    from paper_2605_01255_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    ns = min(lin.n, budget_tokens)
+    X = inputs.as_f64(data["X"][:ns]); W = inputs.as_f64(data["W"]); dY = inputs.as_f64(data["dY"][:ns])
+    t0 = time.perf_counter()
+    Y, Xs = orc.linear_fwd(X, W, lin.seed, lin.r)
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, lin.seed, lin.r, want_dW=with_dw)
+    dt = time.perf_counter() - t0
+    flops = 4 * ns * lin.d_in * lin.d_out + 2 * ns * lin.r * (lin.d_in + lin.d_out)
+    if with_dw:
+        flops += 2 * lin.d_in * lin.r * lin.d_out
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"first {ns} of {lin.n} tokens, fp64 numpy fwd+bwd{'+dW' if with_dw else ''}, {dt:.2f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_01255_amd import binding as acc, inputs
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg, _, which = args.config.partition(".")
+    linears = inputs.config(cfg)
+    if which:
+        linears = [l for l in linears if l.name == args.config]
+    with_dw = not args.no_dw
+    lin = linears[0]                       # the benchmark line is quoted on the first linear of the config
+    data = inputs.make(lin)
+    code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code)
+    sets = [Buffers(acc, torch, lin, data, dev, with_dw) for _ in range(max(1, args.buffer_sets))]
+    ws_f = acc.alloc_workspace(desc, False, dev)
+    ws_b = acc.alloc_workspace(desc, True, dev)
+
+    def fwd(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd(desc, b.X, b.W, b.Y, b.Xs, ws_f)
+
+    def bwd(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_bwd(desc, b.dY, b.W, b.Xs, b.dX, b.Gr, b.dW, ws_b)
+
+    def step(i):
+        fwd(i)
+        bwd(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    flops = lin.flops(with_dw)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if lin.dtype == "bf16" else PEAK_F32_TFLOPS
+
+    # per-phase event timings (same launches, HIP events on the launch stream)
+    ms_fwd = time_events(torch, fwd, args.steps)
+    ms_bwd = time_events(torch, bwd, args.steps)
+    # dominant kernel: the exact-output GEMM Y = X.W, launched alone by a forward with the
+    # sketch skipped (that call enqueues exactly one kernel)
+    desc_gemm = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code,
+                              flags=acc.ACC_FLAG_SKIP_SKETCH)
+
+    def gemm_only(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd(desc_gemm, b.X, b.W, b.Y, None, None)
+
+    gemm_only(0)
+    ms_gemm = time_events(torch, gemm_only, args.steps)
+    gemm_flops = 2 * lin.n * lin.d_in * lin.d_out
+    achieved = gemm_flops / (ms_gemm * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "Y = X.W GEMM (acc_linear_fwd, sketch skipped)",
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4), "traffic": None}
+
+    dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
+    out = {
+        "metric": "compressed-linear fwd+bwd TFLOP/s", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{lin.name}: n={lin.n} tokens, {lin.d_in}->{lin.d_out}, r={lin.r}, "
+                               f"{lin.dtype}, X with {lin.n_outliers} outlier channels x20"
+                               if lin.x_kind == "outlier" else f"{lin.name}: n={lin.n}, {lin.d_in}->{lin.d_out}, r={lin.r}, {lin.dtype}",
+                   "with_dw": with_dw, "buffer_sets": len(sets)},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / peak, 2),
+        "ms_fwd": round(ms_fwd, 4), "ms_bwd": round(ms_bwd, 4),
+        "activation_bytes_per_token": {"dense": dense_b / lin.n, "kept": round(kept_b / lin.n, 4),
+                                       "saved": round((dense_b - kept_b) / lin.n, 4),
+                                       "ratio": round(dense_b / kept_b, 2)},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        budget = 2048 if lin.n * lin.d_in * lin.d_out > 1e10 else lin.n
+        out["cpu_baseline"] = cpu_baseline(lin, data, with_dw, budget)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

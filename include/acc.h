@@ -1,0 +1,113 @@
+/*
+ * acc.h -- C ABI of libacc.so: the compressed linear layer of activation-gradient
+ * co-compression (paper Sec. 4; operator workflow of Def. 3.1) for AMD MI355X (gfx950).
+ *
+ * Notation (row-major everywhere):
+ *   X  [n, d_in]      input activation          W  [d_in, d_out]  weight
+ *   Y  [n, d_out]     exact output  Y = X.W     dY [n, d_out]     incoming gradient
+ *   S  [n, r]         random-projection compressor, i.i.d. N(0, 1/r); NEVER stored:
+ *                     S[i, j] is a pure function of (seed, row_offset + i, j)
+ *   Xs [d_in, r]      Xs = X^T.S   the only activation kept for backward
+ *   dX [n, d_in]      dX = dY.W^T  exact input gradient
+ *   Gr [r, d_out]     Gr = S^T.dY  small factor of the weight gradient
+ *   dW [d_in, d_out]  dW = Xs.Gr   factored weight gradient, materialised on request
+ *
+ * Random stream: Philox4x32-10 with key (seed low word, seed high word) and counter
+ * ((g >> 2) low word, j, 0, g >> 34), g = row_offset + i; output word w of the call is
+ * token 4*(g >> 2) + w of column j.  u = ((x >> 9) + 0.5) * 2^-23; Box-Muller on the word
+ * pairs (x0, x1), (x2, x3): z_even = R cos(theta), z_odd = R sin(theta),
+ * R = sqrt(-2 ln u_first), theta = 2 pi u_second; S = z / sqrt(r).
+ *
+ * Ownership and behaviour common to every call:
+ *   - every data pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps one and never synchronises: a call only enqueues kernels
+ *     on `stream` (a hipStream_t passed as void*; NULL = the default stream);
+ *   - X, W, Y, dY, dX, Xs, Gr, dW and the workspace must be 16-byte aligned;
+ *   - return value 0 = success, negative = one of ACC_ERR_*; on error nothing is launched;
+ *   - no C++ exception crosses this boundary; the library runs on gfx950 only.
+ */
+#ifndef ACC_H_
+#define ACC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { ACC_F32 = 0, ACC_BF16 = 1 } acc_dtype;
+
+enum {
+  ACC_OK = 0,
+  ACC_ERR_INVALID_ARG = -1, /* NULL descriptor or required pointer, unknown flag            */
+  ACC_ERR_SHAPE = -2,       /* a size is <= 0, r % 16 != 0, d_in % 8 or d_out % 8 != 0,
+                               a row stride smaller than the row or not a multiple of 8,
+                               row_offset % 4 != 0                                           */
+  ACC_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                              */
+  ACC_ERR_DTYPE = -4,       /* a dtype field is not ACC_F32 / ACC_BF16                       */
+  ACC_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than acc_linear_workspace_bytes()   */
+  ACC_ERR_HIP = -6          /* HIP runtime error, or the current device is not gfx950        */
+};
+
+enum {
+  ACC_FLAG_SKIP_SKETCH = 1u /* forward only: leave Xs untouched (several linears that share
+                               one input, e.g. q/k/v, keep a single Xs)                      */
+};
+
+typedef struct acc_linear_desc {
+  int64_t n;            /* tokens (batch x sequence)                                         */
+  int64_t d_in;         /* input features,  multiple of 8                                    */
+  int64_t d_out;        /* output features, multiple of 8                                    */
+  int64_t r;            /* sketch rank, multiple of 16                                       */
+  int64_t ldx;          /* row stride of X and dX in elements; 0 = d_in                      */
+  int64_t ldw;          /* row stride of W in elements;        0 = d_out                     */
+  int64_t ldy;          /* row stride of Y and dY in elements; 0 = d_out                     */
+  uint64_t seed;        /* Philox key                                                        */
+  uint64_t row_offset;  /* global index of local token 0 (multiple of 4); 0 on one GPU      */
+  int32_t io_dtype;     /* acc_dtype of X, W, Y, dY, dX                                      */
+  int32_t factor_dtype; /* acc_dtype of Xs and Gr                                            */
+  int32_t dw_dtype;     /* acc_dtype of the dense dW (ignored when dW == NULL)               */
+  uint32_t flags;       /* ACC_FLAG_*                                                        */
+} acc_linear_desc;
+
+/* Bytes of device workspace the forward (is_backward == 0) or backward call needs for the
+ * split-token fp32 partials of the sketch.  Returns 0 for an invalid descriptor. */
+size_t acc_linear_workspace_bytes(const acc_linear_desc* desc, int is_backward);
+
+/* Forward of the compressed linear operator (Def. 3.1: the output is exact, the input is
+ * compressed and stored; Sec. 4: the stored factor).  Computes Y = X.W and, unless
+ * ACC_FLAG_SKIP_SKETCH is set, Xs = X^T.S with S regenerated from (seed, row_offset).
+ * X [n, ldx], W [d_in, ldw] are read; Y [n, ldy] and Xs [d_in, r] (dense) are overwritten.
+ * workspace: ws_bytes >= acc_linear_workspace_bytes(desc, 0); contents are scratch. */
+int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
+                   void* workspace, size_t ws_bytes, void* stream);
+
+/* Backward (Def. 3.1 and Thm 3.2.2(a): dX = dY.W^T is exact; Sec. 4: the weight gradient is
+ * kept as two rank-r factors).  Computes dX [n, ldx], Gr = S^T.dY [r, d_out] (dense) and, when
+ * dW != NULL, the dense dW = Xs.Gr [d_in, d_out] (Sec. 4, update strategy (i)).
+ * dY [n, ldy], W and Xs (as written by acc_linear_fwd with the same seed / row_offset / r)
+ * are read.  Xs may be NULL when dW is NULL. */
+int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, const void* Xs,
+                   void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream);
+
+/* Test hook: the Philox integer stream behind S.  out is a device array of
+ * ceil(n/4) * r * 4 uint32 laid out [token group q][column j][word w]. */
+int acc_philox_dump_u32(uint64_t seed, uint64_t row_offset, int64_t n, int64_t r, uint32_t* out,
+                        void* stream);
+
+/* Test hook: S itself as float32 [n, r] (device), produced by the same device code the layer
+ * kernels use: io_dtype ACC_F32 gives the fp32 generator, ACC_BF16 the fast generator rounded
+ * to bfloat16 and widened.  Only n, r, seed, row_offset and io_dtype of desc are read. */
+int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* acc_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int acc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACC_H_ */

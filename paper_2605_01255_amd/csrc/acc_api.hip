@@ -1,0 +1,271 @@
+// Host side of libacc.so: argument validation, launch planning, kernel launches.
+// No allocation, no synchronisation: every entry point only enqueues on the caller's stream.
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <tuple>
+#include <utility>
+
+#include "acc_common.h"
+#include "acc_generic.h"
+
+namespace acc {
+namespace {
+
+constexpr int kVersion = 100;  // 0.1.0
+
+bool valid_dtype(int32_t d) { return d == ACC_F32 || d == ACC_BF16; }
+size_t dtype_size(int32_t d) { return d == ACC_BF16 ? 2 : 4; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+struct Shape {
+  int64_t n, d_in, d_out, r, ldx, ldw, ldy;
+};
+
+int validate_desc(const acc_linear_desc* d, Shape* s) {
+  if (!d) return ACC_ERR_INVALID_ARG;
+  if (d->flags & ~(uint32_t)ACC_FLAG_SKIP_SKETCH) return ACC_ERR_INVALID_ARG;
+  if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
+    return ACC_ERR_DTYPE;
+  if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
+  if (d->r % 16 || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;
+  if (d->n > (int64_t)1 << 40 || d->d_in > (1 << 21) || d->d_out > (1 << 21) || d->r > (1 << 16))
+    return ACC_ERR_SHAPE;
+  if (d->row_offset % 4) return ACC_ERR_SHAPE;
+  s->n = d->n; s->d_in = d->d_in; s->d_out = d->d_out; s->r = d->r;
+  s->ldx = d->ldx ? d->ldx : d->d_in;
+  s->ldw = d->ldw ? d->ldw : d->d_out;
+  s->ldy = d->ldy ? d->ldy : d->d_out;
+  if (s->ldx < s->d_in || s->ldw < s->d_out || s->ldy < s->d_out) return ACC_ERR_SHAPE;
+  if (s->ldx % 8 || s->ldw % 8 || s->ldy % 8) return ACC_ERR_SHAPE;
+  return ACC_OK;
+}
+
+// ACC_VERBOSE=1 in the environment prints the HIP error behind an ACC_ERR_HIP to stderr.
+int hip_fail(hipError_t e, const char* what) {
+  static const bool verbose = getenv("ACC_VERBOSE") != nullptr;
+  if (verbose) fprintf(stderr, "libacc: %s: %s\n", what, hipGetErrorString(e));
+  return ACC_ERR_HIP;
+}
+
+// The library only runs on gfx950; the answer is cached per device ordinal.
+int check_device() {
+  static int cached[64];  // 0 unknown, 1 ok, -1 not gfx950
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return ACC_ERR_HIP;
+  if (cached[dev] == 0) {
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDeviceProperties");
+    cached[dev] = (strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : -1;
+    if (cached[dev] != 1) hip_fail(hipErrorInvalidDevice, prop.gcnArchName);
+  }
+  return cached[dev] == 1 ? ACC_OK : ACC_ERR_HIP;
+}
+
+// Enqueues kernels on one stream and remembers the first launch error.
+struct Launcher {
+  hipStream_t st;
+  hipError_t err = hipSuccess;
+  template <typename... KArgs, typename... Args>
+  void operator()(void (*kernel)(KArgs...), dim3 grid, dim3 block, Args... args) {
+    if (err != hipSuccess) return;
+    std::tuple<KArgs...> vals{args...};
+    void* ptrs[sizeof...(KArgs)];
+    fill(ptrs, vals, std::index_sequence_for<KArgs...>{});
+    err = hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+  }
+  template <typename T, size_t... I>
+  static void fill(void** ptrs, T& vals, std::index_sequence<I...>) {
+    ((ptrs[I] = (void*)&std::get<I>(vals)), ...);
+  }
+  int status() const { return err == hipSuccess ? ACC_OK : hip_fail(err, "kernel launch"); }
+};
+
+SketchParams make_sketch_params(const acc_linear_desc* d) {
+  SketchParams sk;
+  sk.key0 = (uint32_t)(d->seed & 0xFFFFFFFFu);
+  sk.key1 = (uint32_t)(d->seed >> 32);
+  sk.row_offset = d->row_offset;
+  sk.inv_sqrt_r = (float)(1.0 / sqrt((double)d->r));
+  sk.neg2_ln2_over_r = (float)(-2.0 * 0.6931471805599453 / (double)d->r);
+  return sk;
+}
+
+// ---- generic path --------------------------------------------------------------------------
+// Token splits of the sketch contraction: enough work-groups to fill 256 CUs, at most 32 partials.
+int generic_sketch_splits(int64_t n, int64_t c, int64_t r) {
+  const int64_t tiles = ceil_div(c, 64) * ceil_div(r, 64);
+  int64_t g = ceil_div(1024, tiles);
+  const int64_t max_by_k = ceil_div(n, 256);
+  if (g > max_by_k) g = max_by_k;
+  if (g > 32) g = 32;
+  if (g < 1) g = 1;
+  return (int)g;
+}
+
+template <typename TA, typename TB, typename TC, typename CT, bool SK, bool ACCURATE>
+void launch_generic(const GemmParams& p, int splits, Launcher& L) {
+  dim3 grid((unsigned)ceil_div(p.M, 64), (unsigned)ceil_div(p.N, 64), (unsigned)splits);
+  L(gemm_generic_kernel<TA, TB, TC, CT, SK, ACCURATE>, grid, dim3(256), p);
+}
+
+// C[M, N] = A . B, all three of one storage type.
+void generic_gemm_io(int32_t dt, const GemmParams& p, Launcher& L) {
+  if (dt == ACC_BF16) launch_generic<bf16, bf16, bf16, bf16, false, false>(p, 1, L);
+  else launch_generic<float, float, float, float, false, true>(p, 1, L);
+}
+
+// partial[g][...] = A^T-slab . S-slab, fp32, then K4 reduce into `out` (factor dtype).
+void generic_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
+                    int64_t c_sm, int64_t c_sn, void* out, float* ws, Launcher& L) {
+  GemmParams p{};
+  p.A = A; p.B = nullptr; p.C = ws;
+  p.M = channels; p.N = d->r; p.K = n;
+  p.a_sm = 1; p.a_sk = lda;
+  p.c_sm = c_sm; p.c_sn = c_sn;
+  const int G = generic_sketch_splits(n, channels, d->r);
+  p.k_per_split = round_up(ceil_div(n, G), 32);
+  p.c_split_stride = channels * d->r;
+  p.sk = make_sketch_params(d);
+  if (d->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, bf16, true, false>(p, G, L);
+  else launch_generic<float, float, float, float, true, true>(p, G, L);
+  const int64_t count = channels * d->r;
+  const unsigned blocks = (unsigned)ceil_div(count, 1024);
+  if (d->factor_dtype == ACC_BF16)
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (bf16*)out);
+  else
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (float*)out);
+}
+
+void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const void* Gr, void* dW, Launcher& L) {
+  GemmParams p{};
+  p.A = Xs; p.B = Gr; p.C = dW;
+  p.M = s.d_in; p.N = s.d_out; p.K = s.r;
+  p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
+  p.k_per_split = round_up(s.r, 32);
+  const bool fb = d->factor_dtype == ACC_BF16, ob = d->dw_dtype == ACC_BF16;
+  if (fb && ob) launch_generic<bf16, bf16, bf16, bf16, false, false>(p, 1, L);
+  else if (fb) launch_generic<bf16, bf16, float, bf16, false, false>(p, 1, L);
+  else if (ob) launch_generic<float, float, bf16, float, false, true>(p, 1, L);
+  else launch_generic<float, float, float, float, false, true>(p, 1, L);
+}
+
+size_t workspace_bytes(const acc_linear_desc* d, const Shape& s, bool backward) {
+  const int64_t channels = backward ? s.d_out : s.d_in;
+  const int G = generic_sketch_splits(s.n, channels, s.r);
+  return (size_t)G * (size_t)channels * (size_t)s.r * sizeof(float);
+}
+
+}  // namespace
+}  // namespace acc
+
+using namespace acc;
+
+extern "C" {
+
+size_t acc_linear_workspace_bytes(const acc_linear_desc* desc, int is_backward) {
+  Shape s;
+  if (validate_desc(desc, &s) != ACC_OK) return 0;
+  return workspace_bytes(desc, s, is_backward != 0);
+}
+
+int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
+                   void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  const bool sketch = !(desc->flags & ACC_FLAG_SKIP_SKETCH);
+  if (!X || !W || !Y || (sketch && !Xs)) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(Xs) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  if (sketch && (!workspace || ws_bytes < workspace_bytes(desc, s, false))) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+
+  GemmParams p{};
+  p.A = X; p.B = W; p.C = Y;
+  p.M = s.n; p.N = s.d_out; p.K = s.d_in;
+  p.a_sm = s.ldx; p.a_sk = 1; p.b_sk = s.ldw; p.b_sn = 1; p.c_sm = s.ldy; p.c_sn = 1;
+  p.k_per_split = round_up(s.d_in, 32);
+  generic_gemm_io(desc->io_dtype, p, L);
+  if (sketch) generic_sketch(desc, X, s.ldx, s.d_in, s.n, s.r, 1, Xs, (float*)workspace, L);
+  return L.status();
+}
+
+int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, const void* Xs,
+                   void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (desc->flags & ACC_FLAG_SKIP_SKETCH) return ACC_ERR_INVALID_ARG;
+  if (!dY || !W || !dX || !Gr || (dW && !Xs)) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(W) || !aligned16(Xs) || !aligned16(dX) || !aligned16(Gr) ||
+      !aligned16(dW) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  if (!workspace || ws_bytes < workspace_bytes(desc, s, true)) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+
+  GemmParams p{};
+  p.A = dY; p.B = W; p.C = dX;
+  p.M = s.n; p.N = s.d_in; p.K = s.d_out;
+  p.a_sm = s.ldy; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.ldw; p.c_sm = s.ldx; p.c_sn = 1;
+  p.k_per_split = round_up(s.d_out, 32);
+  generic_gemm_io(desc->io_dtype, p, L);
+  // Gr[j, c] = sum_i S[i, j] dY[i, c]: the contraction of dY^T with S, stored transposed.
+  generic_sketch(desc, dY, s.ldy, s.d_out, s.n, 1, s.d_out, Gr, (float*)workspace, L);
+  if (dW) generic_dw(desc, s, Xs, Gr, dW, L);
+  return L.status();
+}
+
+int acc_philox_dump_u32(uint64_t seed, uint64_t row_offset, int64_t n, int64_t r, uint32_t* out,
+                        void* stream) {
+  if (!out) return ACC_ERR_INVALID_ARG;
+  if (n <= 0 || r <= 0 || row_offset % 4) return ACC_ERR_SHAPE;
+  if (!aligned16(out)) return ACC_ERR_ALIGN;
+  int rc = check_device();
+  if (rc != ACC_OK) return rc;
+  const int64_t nq = (n + 3) / 4;
+  Launcher L{(hipStream_t)stream};
+  L(philox_dump_kernel, dim3((unsigned)ceil_div(nq * r, 256)), dim3(256), (uint32_t)(seed & 0xFFFFFFFFu),
+    (uint32_t)(seed >> 32), row_offset, nq, r, out);
+  return L.status();
+}
+
+int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream) {
+  if (!desc || !S) return ACC_ERR_INVALID_ARG;
+  if (!valid_dtype(desc->io_dtype)) return ACC_ERR_DTYPE;
+  if (desc->n <= 0 || desc->r <= 0 || desc->row_offset % 4) return ACC_ERR_SHAPE;
+  if (!aligned16(S)) return ACC_ERR_ALIGN;
+  int rc = check_device();
+  if (rc != ACC_OK) return rc;
+  const int64_t nq = (desc->n + 3) / 4;
+  const dim3 grid((unsigned)ceil_div(nq * desc->r, 256));
+  const SketchParams sk = make_sketch_params(desc);
+  Launcher L{(hipStream_t)stream};
+  if (desc->io_dtype == ACC_F32) L(sketch_dump_kernel<true>, grid, dim3(256), sk, desc->n, desc->r, S);
+  else L(sketch_dump_kernel<false>, grid, dim3(256), sk, desc->n, desc->r, S);
+  return L.status();
+}
+
+const char* acc_status_string(int status) {
+  switch (status) {
+    case ACC_OK: return "ACC_OK";
+    case ACC_ERR_INVALID_ARG: return "ACC_ERR_INVALID_ARG: null descriptor/pointer or unknown flag";
+    case ACC_ERR_SHAPE: return "ACC_ERR_SHAPE: unsupported size, stride or row_offset";
+    case ACC_ERR_ALIGN: return "ACC_ERR_ALIGN: pointer not 16-byte aligned";
+    case ACC_ERR_DTYPE: return "ACC_ERR_DTYPE: unknown dtype";
+    case ACC_ERR_WORKSPACE: return "ACC_ERR_WORKSPACE: workspace missing or too small";
+    case ACC_ERR_HIP: return "ACC_ERR_HIP: HIP runtime error or device is not gfx950";
+    default: return "ACC_ERR_UNKNOWN";
+  }
+}
+
+int acc_version(void) { return kVersion; }
+
+}  // extern "C"

@@ -86,8 +86,8 @@ class Linear:
 
 
 def outlier_channels(d_in: int, k: int):
-    """Channel indices that carry the x20 outliers: c_j = j * (d_in // k) + 5."""
-    return [j * (d_in // k) + 5 for j in range(k)]
+    """Channel indices that carry the x20 outliers: c_j = j * (d_in // k) + 5 (wrapped for tiny d_in)."""
+    return sorted({(j * (d_in // k) + 5) % d_in for j in range(k)})
 
 
 def _rng(data_seed: int, tag: int) -> np.random.Generator:

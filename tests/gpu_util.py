@@ -1,0 +1,84 @@
+"""Helpers for the GPU parity tests: run the layer through the C ABI, run the oracle, compare."""
+import numpy as np
+
+from paper_2605_01255_amd import inputs
+from oracle import acc_oracle as orc
+
+
+def rel(a, b):
+    """Relative Frobenius error of a against the oracle value b."""
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a))
+
+
+def tolerance(dtype_code):
+    """The spec bar: 1e-2 for bfloat16 outputs, 1e-5 for float32 outputs."""
+    return 1e-2 if dtype_code == 1 else 1e-5
+
+
+def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, row_offset=0,
+              pad=(0, 0, 0), flags=0, seed=None, device="cuda:0"):
+    """One forward + backward through acc_linear_fwd / acc_linear_bwd.  Returns float64 arrays."""
+    import torch
+    code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
+    fcode = code if factor_dtype is None else factor_dtype
+    dcode = code if dw_dtype is None else dw_dtype
+    seed = lin.seed if seed is None else seed
+    tdt = acc.torch_dtype(code)
+    ldx, ldw, ldy = lin.d_in + pad[0], lin.d_out + pad[1], lin.d_out + pad[2]
+
+    def padded(arr, ld):
+        t = acc.to_device(arr, device)
+        if ld == arr.shape[1]:
+            return t, t
+        buf = torch.full((arr.shape[0], ld), float("nan"), dtype=t.dtype, device=device)
+        buf[:, :arr.shape[1]] = t
+        return buf, buf
+
+    X, _ = padded(data["X"], ldx)
+    W, _ = padded(data["W"], ldw)
+    dY, _ = padded(data["dY"], ldy)
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
+                         dw_dtype=dcode, row_offset=row_offset, ldx=ldx if pad[0] else 0,
+                         ldw=ldw if pad[1] else 0, ldy=ldy if pad[2] else 0, flags=flags)
+    Y = torch.full((lin.n, ldy), 7.0, dtype=tdt, device=device)
+    dX = torch.full((lin.n, ldx), 7.0, dtype=tdt, device=device)
+    Xs = torch.full((lin.d_in, lin.r), 7.0, dtype=acc.torch_dtype(fcode), device=device)
+    Gr = torch.full((lin.r, lin.d_out), 7.0, dtype=acc.torch_dtype(fcode), device=device)
+    dW = torch.full((lin.d_in, lin.d_out), 7.0, dtype=acc.torch_dtype(dcode), device=device) if want_dw else None
+    acc.acc_linear_fwd(desc, X, W, Y, Xs, acc.alloc_workspace(desc, False, device))
+    bdesc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
+                          dw_dtype=dcode, row_offset=row_offset, ldx=desc.ldx, ldw=desc.ldw, ldy=desc.ldy)
+    acc.acc_linear_bwd(bdesc, dY, W, Xs, dX, Gr, dW, acc.alloc_workspace(bdesc, True, device))
+    torch.cuda.synchronize()
+    out = {"Y": acc.to_host_f64(Y), "Xs": acc.to_host_f64(Xs), "dX": acc.to_host_f64(dX),
+           "Gr": acc.to_host_f64(Gr)}
+    if want_dw:
+        out["dW"] = acc.to_host_f64(dW)
+    # padding columns must be untouched
+    if pad[2]:
+        assert np.all(out["Y"][:, lin.d_out:] == 7.0)
+        out["Y"] = out["Y"][:, :lin.d_out]
+    if pad[0]:
+        assert np.all(out["dX"][:, lin.d_in:] == 7.0)
+        out["dX"] = out["dX"][:, :lin.d_in]
+    return out
+
+
+def run_oracle(lin, data, want_dw=True, row_offset=0, seed=None):
+    seed = lin.seed if seed is None else seed
+    X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+    S = orc.sketch_matrix(seed, lin.n, lin.r, row_offset)
+    Y, Xs = orc.linear_fwd(X, W, S=S)
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=S, want_dW=want_dw)
+    out = {"Y": Y, "Xs": Xs, "dX": dX, "Gr": Gr}
+    if want_dw:
+        out["dW"] = dW
+    return out
+
+
+def compare(got, want, tol, names=None):
+    errs = {k: rel(got[k], want[k]) for k in (names or want.keys())}
+    bad = {k: v for k, v in errs.items() if not v <= tol[k] if isinstance(tol, dict)} if isinstance(tol, dict) \
+        else {k: v for k, v in errs.items() if not v <= tol}
+    return errs, bad

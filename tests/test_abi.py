@@ -1,0 +1,110 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/acc.h declares,
+the ctypes mirror of the descriptor matches the header, and invalid calls are refused before
+anything touches a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "acc.h")
+
+acc = pytest.importorskip("paper_2605_01255_amd.binding", reason="libacc.so not built")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(acc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared_functions()
+    assert set(names) == set(acc.EXPORTS)
+    lib = ctypes.CDLL(acc.LIB_PATH)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_descriptor_layout_matches_header():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct acc_linear_desc \{(.*?)\} acc_linear_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(int64_t|uint64_t|int32_t|uint32_t)\s+(\w+)\s*;", body)
+    ctype = {"int64_t": ctypes.c_int64, "uint64_t": ctypes.c_uint64, "int32_t": ctypes.c_int32,
+             "uint32_t": ctypes.c_uint32}
+    assert [(n, ctype[t]) for t, n in fields] == list(acc.AccLinearDesc._fields_)
+    assert ctypes.sizeof(acc.AccLinearDesc) == 88
+
+
+def test_version_and_status_strings():
+    assert acc.acc_version() >= 100
+    assert acc.status_string(0) == "ACC_OK"
+    for code in range(-6, 0):
+        assert acc.status_string(code).startswith("ACC_ERR_")
+    assert acc.status_string(-99) == "ACC_ERR_UNKNOWN"
+
+
+def _fwd(desc, X=0x1000, W=0x2000, Y=0x3000, Xs=0x4000, ws=0x5000, ws_bytes=1 << 40):
+    return acc._lib.acc_linear_fwd(ctypes.byref(desc), X, W, Y, Xs, ws, ws_bytes, None)
+
+
+def _bwd(desc, dY=0x1000, W=0x2000, Xs=0x4000, dX=0x3000, Gr=0x6000, dW=0x7000, ws=0x5000, ws_bytes=1 << 40):
+    return acc._lib.acc_linear_bwd(ctypes.byref(desc), dY, W, Xs, dX, Gr, dW, ws, ws_bytes, None)
+
+
+def test_invalid_descriptors_are_refused():
+    ok = dict(n=256, d_in=256, d_out=512, r=16)
+    assert acc._lib.acc_linear_fwd(None, 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1 << 30, None) == -1
+    for bad in (dict(n=0), dict(d_in=0), dict(r=0), dict(r=24), dict(d_in=252), dict(d_out=516),
+                dict(row_offset=2), dict(ldx=128), dict(ldx=260), dict(ldy=8), dict(n=-5)):
+        d = acc.make_desc(**{**ok, **bad})
+        assert _fwd(d) == -2, bad
+        assert _bwd(d) == -2, bad
+        assert acc.acc_linear_workspace_bytes(d, False) == 0
+    assert _fwd(acc.make_desc(**ok, io_dtype=7)) == -4
+    assert _fwd(acc.make_desc(**ok, factor_dtype=-1)) == -4
+    assert _fwd(acc.make_desc(**ok, flags=8)) == -1
+    assert _bwd(acc.make_desc(**ok, flags=acc.ACC_FLAG_SKIP_SKETCH)) == -1
+
+
+def test_pointer_and_workspace_checks():
+    d = acc.make_desc(256, 256, 512, 16, io_dtype=acc.ACC_F32)
+    assert _fwd(d, X=0) == -1 and _fwd(d, Y=0) == -1 and _fwd(d, Xs=0) == -1
+    assert _fwd(d, X=0x1004) == -3 and _fwd(d, Xs=0x4008) == -3 and _fwd(d, ws=0x5002) == -3
+    need = acc.acc_linear_workspace_bytes(d, False)
+    assert need >= 256 * 16 * 4
+    assert _fwd(d, ws_bytes=need - 1) == -5 and _fwd(d, ws=0) == -5
+    assert _bwd(d, dY=0) == -1 and _bwd(d, Gr=0) == -1 and _bwd(d, Xs=0) == -1
+    assert _bwd(d, dW=0x7004) == -3
+    needb = acc.acc_linear_workspace_bytes(d, True)
+    assert _bwd(d, ws_bytes=needb - 1) == -5
+    # Xs may be NULL when no dense dW is requested: passes validation (then needs a device)
+    assert _bwd(d, Xs=0, dW=0) in (0, -6)
+
+
+def test_hooks_validate_arguments():
+    assert acc._lib.acc_philox_dump_u32(0, 0, 16, 16, None, None) == -1
+    assert acc._lib.acc_philox_dump_u32(0, 2, 16, 16, 0x1000, None) == -2
+    assert acc._lib.acc_philox_dump_u32(0, 0, 0, 16, 0x1000, None) == -2
+    assert acc._lib.acc_philox_dump_u32(0, 0, 16, 16, 0x1004, None) == -3
+    d = acc.make_desc(16, 8, 8, 16)
+    assert acc._lib.acc_sketch_dump(ctypes.byref(d), None, None) == -1
+    assert acc._lib.acc_sketch_dump(None, 0x1000, None) == -1
+
+
+def test_without_a_gfx950_device_calls_fail_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    d = acc.make_desc(256, 256, 512, 16, io_dtype=acc.ACC_F32)
+    assert _fwd(d) == -6
+    with pytest.raises(acc.AccError):
+        acc._check(_fwd(d))
+
+
+def test_workspace_query_is_positive_and_monotone_in_rank():
+    a = acc.acc_linear_workspace_bytes(acc.make_desc(16384, 3072, 3072, 64), False)
+    b = acc.acc_linear_workspace_bytes(acc.make_desc(16384, 3072, 3072, 256), False)
+    assert 0 < a <= b
