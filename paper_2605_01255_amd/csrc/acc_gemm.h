@@ -1,0 +1,333 @@
+// Tuned bf16 MFMA GEMM for gfx950 (steps F1, B1, B3):  C[M, N] = A[M, K] . B, fp32 accumulate.
+//
+//   A is row-major with K contiguous (X, dY, Xs).
+//   B_KMAJOR = true : B is given as Bt[N, K], K contiguous      (dX = dY . W^T reads W as is)
+//   B_KMAJOR = false: B is given as  B[K, N], N contiguous      (Y = X . W, dW = Xs . Gr); the MFMA
+//                     operand is formed with transposing LDS reads (ds_read_b64_tr_b16).
+//
+// Work-group tile (WM*TM*32) x (WN*TN*32) x 64, WM x WN waves, each wave TM x TN MFMA 32x32x16 tiles.
+// Tiles travel global -> LDS directly (global_load_lds_dwordx4, no staging registers); LDS is double
+// buffered, one barrier per K tile, and the MFMAs run one k-step behind the LDS reads so that the
+// reads after the barrier are covered by the last k-step of the previous tile.
+// K % 64 == 0; M and N arbitrary (loads past the last row read zero through the buffer resource,
+// stores are predicated); N % 8 == 0; every operand smaller than 4 GiB.
+#pragma once
+#include <type_traits>
+
+#include "acc_common.h"
+
+namespace acc {
+
+struct FastGemmParams {
+  const bf16* A;
+  const bf16* B;
+  void* C;
+  int64_t M, N, K;
+  int64_t lda, ldb, ldc;  // row strides in elements
+  int tiles_m, tiles_n;   // work-group tiles along M and N
+  int super_m, super_n;   // XCD super-tile shape (in tiles), super_m * super_n == 32
+  int supers_n;           // super-tiles along N
+};
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// LDS layout of a K-contiguous tile: 128-byte rows (64 bf16), 16-byte chunk c of row `row` stored at
+// chunk position c ^ swz(row).  The LDS has 64 four-byte banks, so two consecutive rows cover the
+// whole bank window; (row >> 1) & 7 makes 16 consecutive rows reading one logical chunk hit 16
+// different bank groups (ds_read_b128 serves 16 lanes per clock).
+__device__ __forceinline__ int swz(int row) { return (row >> 1) & 7; }
+
+// LDS layout of an N-contiguous B tile: rows of BN bf16 (one k each), 16-byte chunk c of row k stored
+// at chunk position c ^ ((k & 3) << 2): the 4 k-rows x 2 column groups that 32 lanes of a transposing
+// read touch fall on 8 different 32-byte bank groups.
+__device__ __forceinline__ int swz_n(int krow) { return (krow & 3) << 2; }
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const char* lds, int byte_off) {
+  return *(const bf16x8*)(lds + byte_off);
+}
+
+// 4 x 16 transposed read: the 16 lanes of a group give 4 rows x 4 chunks of 4 elements; lane l of the
+// group receives element l of each of the 4 rows.
+__device__ __forceinline__ s16x4 lds_read_tr16_b64(const char* lds, int byte_off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (s16x4 __attribute__((address_space(3)))*)(uintptr_t)(uint32_t)(uintptr_t)(lds + byte_off));
+}
+
+// Buffer resource over [base, base + bytes): loads beyond `bytes` return zero instead of faulting.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+  const uint32_t n = bytes > 0xFFFFFFFFll ? 0xFFFFFFFFu : (bytes < 0 ? 0u : (uint32_t)bytes);
+  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, n, 0x00020000);  // raw buffer, 32-bit format
+}
+
+// 64 lanes x 16 bytes, global -> LDS without passing through registers (buffer_load_dwordx4 ... lds).
+// Lane i reads rsrc[voffset_i + soffset] and lands at lds_wave_base + 16 * i (lds_wave_base and
+// soffset wave-uniform); counted by vmcnt.
+__device__ __forceinline__ void buffer_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset,
+                                                   uint32_t soffset, char* lds_wave_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds_wave_base, 16,
+                                           voffset, soffset, 0, 0);
+}
+
+// s_waitcnt vmcnt(0) (expcnt / lgkmcnt untouched): all global -> LDS transfers of this wave landed.
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+
+// Map the linear work-group id to an output tile so that the 32 tiles resident on one XCD
+// (work-groups are dealt round-robin to the 8 XCDs) form a super_m x super_n block that shares
+// A and B panels in that XCD's L2.  Returns false for padding work-groups.
+__device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int& tm, int& tn) {
+  const int b = blockIdx.x;
+  const int xcd = b & 7, local = b >> 3;
+  const int sid = (local >> 5) * 8 + xcd;  // super-tile id, N fastest
+  const int in = local & 31;
+  const int sm = sid / p.supers_n, sn = sid - sm * p.supers_n;
+  tm = sm * p.super_m + in % p.super_m;
+  tn = sn * p.super_n + in / p.super_m;
+  return tm < p.tiles_m && tn < p.tiles_n;
+}
+
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
+  constexpr int NW = WM * WN;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
+  constexpr int A_BYTES = BM * BK * 2;
+  constexpr int B_BYTES = BN * BK * 2;
+  constexpr int STAGE = A_BYTES + B_BYTES;
+  constexpr int A_LOADS = A_BYTES / 1024 / NW;  // 1 KB wave-loads per wave and K tile
+  constexpr int B_LOADS = B_BYTES / 1024 / NW;
+  constexpr int BN_CHUNKS = BN / 8;             // 16-byte chunks per row of an N-contiguous B tile
+  static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile/waves");
+  static_assert(B_KMAJOR || (BN_CHUNKS >= 16 && 64 % BN_CHUNKS == 0), "B tile shape");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  int tm, tn;
+  if (!xcd_tile(p, tm, tn)) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+  // ---- global source of every 16-byte chunk this lane moves ----
+  // Wave-load t of wave w fills LDS bytes [(t * NW + w) * 1024, +1024) of the operand's tile: lane i
+  // supplies the chunk that belongs at position i of that kilobyte.  Sources are byte offsets into
+  // buffer resources that start at the tile's first row / column; rows past the end of the matrix
+  // read as zero (their products are never stored).
+  const int64_t am0 = DBG == 7 ? 0 : m0, bn0 = DBG == 7 ? 0 : n0;
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A + am0 * p.lda, ((p.M - am0 - 1) * p.lda + p.K) * 2);
+  const __amdgpu_buffer_rsrc_t b_rsrc =
+      B_KMAJOR ? make_rsrc(p.B + bn0 * p.ldb, ((p.N - bn0 - 1) * p.ldb + p.K) * 2)
+               : make_rsrc(p.B + bn0, ((p.K - 1) * p.ldb + (p.N - bn0)) * 2);
+  uint32_t a_src[A_LOADS];
+#pragma unroll
+  for (int t = 0; t < A_LOADS; ++t) {
+    const int row = (t * NW + wave) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ swz(row);
+    a_src[t] = (uint32_t)(row * p.lda * 2 + c * 16);
+  }
+  uint32_t b_src[B_LOADS];
+#pragma unroll
+  for (int t = 0; t < B_LOADS; ++t) {
+    if (B_KMAJOR) {
+      const int row = (t * NW + wave) * 8 + (lane >> 3);
+      const int c = (lane & 7) ^ swz(row);
+      b_src[t] = (uint32_t)(row * p.ldb * 2 + c * 16);
+    } else {
+      constexpr int ROWS = 64 / BN_CHUNKS;  // k-rows per wave-load
+      const int krow = (t * NW + wave) * ROWS + lane / BN_CHUNKS;
+      const int c = (lane % BN_CHUNKS) ^ swz_n(krow);
+      b_src[t] = (uint32_t)(krow * p.ldb * 2 + c * 16);
+    }
+  }
+  const uint32_t b_kstep = B_KMAJOR ? BK * 2 : (uint32_t)(BK * p.ldb * 2);  // bytes per K tile
+
+  auto issue_loads = [&](int kt, char* stage) {
+#pragma unroll
+    for (int t = 0; t < A_LOADS; ++t)
+      buffer_to_lds_b128(a_rsrc, a_src[t], (uint32_t)kt * (BK * 2), stage + (t * NW + wave) * 1024);
+#pragma unroll
+    for (int t = 0; t < B_LOADS; ++t)
+      buffer_to_lds_b128(b_rsrc, b_src[t], (uint32_t)kt * b_kstep, stage + A_BYTES + (t * NW + wave) * 1024);
+  };
+
+  // ---- LDS read offsets of this lane's MFMA operands ----
+  const int lrow = lane & 31, kg = lane >> 5;
+  int a_rd[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a_rd[i] = (wm * TM * 32 + i * 32 + lrow) * 128;
+  int b_rd[TN][2];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    if (B_KMAJOR) {
+      b_rd[j][0] = b_rd[j][1] = A_BYTES + (wn * TN * 32 + j * 32 + lrow) * 128;
+    } else {
+      // 16-lane group g = lane / 16: columns 16 * (g & 1) .., k rows 8 * (g >> 1) ..; lane i of the
+      // group reads k row i / 4 (+ 4 for the second half), 4-element chunk i % 4.
+      const int g = lane >> 4, i16 = lane & 15;
+      const int n_off = (wn * TN + j) * 32 + 16 * (g & 1) + 4 * (i16 & 3);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int krow = 8 * (g >> 1) + 4 * h + (i16 >> 2);
+        b_rd[j][h] = A_BYTES + krow * (BN * 2) + (((n_off >> 3) ^ swz_n(krow)) << 4) + (n_off & 7) * 2;
+      }
+    }
+  }
+  const int a_swz = swz(lrow);  // rows i * 32 + lrow share swz(lrow)
+
+  auto load_a = [&](const char* cur, int s, bf16x8(&af)[TM], bool force = false) {
+    if (DBG == 5 && !force) return;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[i] = lds_read_b128(cur, a_rd[i] + (((2 * s + kg) ^ a_swz) << 4));
+  };
+  auto load_b = [&](const char* cur, int s, bf16x8(&bfr)[TN], bool force = false) {
+    if (DBG == 5 && !force) return;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      if (B_KMAJOR) {
+        bfr[j] = lds_read_b128(cur, b_rd[j][0] + (((2 * s + kg) ^ a_swz) << 4));
+      } else {
+        const s16x4 lo = lds_read_tr16_b64(cur, b_rd[j][0] + 16 * s * (BN * 2));
+        const s16x4 hi = lds_read_tr16_b64(cur, b_rd[j][1] + 16 * s * (BN * 2));
+        bfr[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  auto mfma_step = [&](const bf16x8(&af)[TM], const bf16x8(&bfr)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        else acc[i][j][0] += (float)af[i][0] * (float)bfr[j][0];
+      }
+  };
+
+  const int KT = (int)(p.K / BK);
+  bf16x8 af[2][TM], bfr[2][TN];
+
+  auto read_a1 = [&](const char* st, int s, int i, bf16x8(&dst)[TM]) {
+    dst[i] = lds_read_b128(st, a_rd[i] + (((2 * s + kg) ^ a_swz) << 4));
+  };
+  auto read_b1 = [&](const char* st, int s, int j, bf16x8(&dst)[TN]) {
+    if (B_KMAJOR) {
+      dst[j] = lds_read_b128(st, b_rd[j][0] + (((2 * s + kg) ^ a_swz) << 4));
+    } else {
+      const s16x4 lo = lds_read_tr16_b64(st, b_rd[j][0] + 16 * s * (BN * 2));
+      const s16x4 hi = lds_read_tr16_b64(st, b_rd[j][1] + 16 * s * (BN * 2));
+      dst[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+  };
+  auto issue_one = [&](int g, int kt, char* stage) {  // g-th wave-load of a K tile (A first, then B)
+    if (g < A_LOADS) buffer_to_lds_b128(a_rsrc, a_src[g], (uint32_t)kt * (BK * 2), stage + (g * NW + wave) * 1024);
+    else buffer_to_lds_b128(b_rsrc, b_src[g - A_LOADS], (uint32_t)kt * b_kstep,
+                            stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024);
+  };
+
+  // One k-step with a fixed instruction order: MFMA q of the step carries (at most) one operand read
+  // for the next step and, every G_EVERY MFMAs, one global->LDS wave-load of the next tile.  Fences
+  // keep the compiler from clustering the memory instructions, which stalls the wave in VMEM issue
+  // while the texture path drains and starves the MFMA pipe.
+  constexpr int NM = TM * TN;
+  constexpr int NG_TOTAL = A_LOADS + B_LOADS;
+  constexpr int G_STEPS = 3;                                   // k-steps that carry wave-loads
+  constexpr int G_PER_STEP = (NG_TOTAL + G_STEPS - 1) / G_STEPS;
+  constexpr int G_EVERY = NM / G_PER_STEP > 0 ? NM / G_PER_STEP : 1;
+  auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s,
+                   bf16x8(&na)[TM], bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, char* nxt) {
+#pragma unroll
+    for (int q = 0; q < NM; ++q) {
+      const int i = q / TN, j = q % TN;
+      if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      else acc[i][j][0] += (float)ca[i][0] * (float)cb[j][0];
+      if (DBG != 5 && DBG != 9) {
+        if (q < TM) read_a1(rd_stage, rd_s, q, na);
+        else if (q < TM + TN) read_b1(rd_stage, rd_s, q - TM, nb);
+      }
+      if (DBG != 1 && DBG != 5 && DBG != 6 && DBG != 9) {
+        if (q % G_EVERY == 0 && q / G_EVERY < g_count && g_first + q / G_EVERY < NG_TOTAL)
+          issue_one(g_first + q / G_EVERY, kt_next, nxt);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  // prologue: tile 0 -> stage 0, operands of its first k-step -> registers
+  issue_loads(0, smem);
+  wait_vmcnt0();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < TM; ++i) read_a1(smem, 0, i, af[0]);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) read_b1(smem, 0, j, bfr[0]);
+  if (DBG == 5) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) read_a1(smem, 1, i, af[1]);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) read_b1(smem, 1, j, bfr[1]);
+  }
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const char* cur = smem + (kt & 1) * STAGE;
+    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    // Branch-free body: the last iteration re-loads its own tile into the idle stage, unused.
+    const int kt_next = kt + 1 < KT ? kt + 1 : kt;
+    __builtin_amdgcn_sched_barrier(0);
+    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
+    // The next tile must have landed (every wave's transfers) before anyone reads it, and every
+    // wave must be done reading `cur` before the tile after next is written over it.
+    wait_vmcnt0();
+    if (DBG != 6) __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    // last k-step of this tile covers the latency of the first operand reads of the next one
+    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt);
+  }
+
+  // ---- epilogue: lane holds column (lane & 31), rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4 ----
+  TC* __restrict__ C = (TC*)p.C;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int64_t gn = n0 + (wn * TN + j) * 32 + lrow;
+      if (gn < p.N) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int64_t gm = m0 + (wm * TM + i) * 32 + (e >> 2) * 8 + kg * 4 + (e & 3);
+          if (gm < p.M && ((DBG != 8 && DBG != 9) || acc[i][j][e] == 1234.5f)) C[gm * p.ldc + gn] = from_f32<TC>(acc[i][j][e]);
+        }
+      }
+    }
+  }
+}
+
+template <int WM, int WN, int TM, int TN>
+constexpr int gemm_bf16_lds_bytes() {
+  return 2 * (WM * TM * 32 + WN * TN * 32) * 64 * 2;
+}
+
+// Fill the tiling fields of p for a BM x BN work-group tile; returns the 1-D grid size.
+static inline unsigned gemm_bf16_plan(FastGemmParams& p, int BM, int BN) {
+  p.tiles_m = (int)ceil_div(p.M, BM);
+  p.tiles_n = (int)ceil_div(p.N, BN);
+  // 32 tiles per XCD at a time: prefer 8 x 4, shrink along a short dimension
+  int sn = p.tiles_n >= 4 ? 4 : (p.tiles_n >= 2 ? 2 : 1);
+  int sm = 32 / sn;
+  p.super_m = sm;
+  p.super_n = sn;
+  p.supers_n = (int)ceil_div(p.tiles_n, sn);
+  const int supers_m = (int)ceil_div(p.tiles_m, sm);
+  const int supers = round_up((int64_t)supers_m * p.supers_n, 8);
+  return (unsigned)(supers * 32);
+}
+
+}  // namespace acc
