@@ -9,7 +9,9 @@
 #include <utility>
 
 #include "acc_common.h"
+#include "acc_gemm.h"
 #include "acc_generic.h"
+#include "acc_sketch.h"
 
 namespace acc {
 namespace {
@@ -73,11 +75,20 @@ struct Launcher {
   hipError_t err = hipSuccess;
   template <typename... KArgs, typename... Args>
   void operator()(void (*kernel)(KArgs...), dim3 grid, dim3 block, Args... args) {
+    launch_lds(kernel, grid, block, 0, args...);
+  }
+  // lds_bytes of dynamic LDS; above 64 KB the kernel's limit is raised first (no allocation involved).
+  template <typename... KArgs, typename... Args>
+  void launch_lds(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, Args... args) {
     if (err != hipSuccess) return;
+    if (lds_bytes > 64 * 1024) {
+      err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (err != hipSuccess) return;
+    }
     std::tuple<KArgs...> vals{args...};
     void* ptrs[sizeof...(KArgs)];
     fill(ptrs, vals, std::index_sequence_for<KArgs...>{});
-    err = hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, st);
+    err = hipLaunchKernel((const void*)kernel, grid, block, ptrs, lds_bytes, st);
   }
   template <typename T, size_t... I>
   static void fill(void** ptrs, T& vals, std::index_sequence<I...>) {
@@ -155,10 +166,101 @@ void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const 
   else launch_generic<float, float, float, float, false, true>(p, 1, L);
 }
 
+// ---- tuned bf16 path ------------------------------------------------------------------------
+constexpr int64_t kMaxOperandBytes = 0xFFFFFFFFll;  // buffer resources address 4 GiB
+
+// C[M, N] = A[M, K] . B with the tuned kernel; B is [N, K] (KMAJ) or [K, N].
+bool fast_gemm_ok(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
+  return K % 64 == 0 && N % 8 == 0 && M * lda * 2 <= kMaxOperandBytes &&
+         (N > K ? N : K) * ldb * 2 <= kMaxOperandBytes && 256 * lda * 2 <= kMaxOperandBytes;
+}
+
+template <bool KMAJ, typename TC>
+void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda,
+               int64_t ldb, int64_t ldc, Launcher& L) {
+  FastGemmParams p{};
+  p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
+  if (big_tiles >= 192) {  // 256 x 256 tiles, 8 waves: enough tiles to fill 256 CUs
+    const unsigned grid = gemm_bf16_plan(p, 256, 256);
+    L.launch_lds(gemm_bf16_kernel<2, 4, 4, 2, KMAJ, TC, 0>, dim3(grid), dim3(512),
+                 (size_t)gemm_bf16_lds_bytes<2, 4, 4, 2>(), p);
+  } else {                 // 128 x 128 tiles, 4 waves
+    const unsigned grid = gemm_bf16_plan(p, 128, 128);
+    L.launch_lds(gemm_bf16_kernel<2, 2, 2, 2, KMAJ, TC, 0>, dim3(grid), dim3(256),
+                 (size_t)gemm_bf16_lds_bytes<2, 2, 2, 2>(), p);
+  }
+}
+
+// Plan of the tuned sketch kernel for `channels` columns of a [n, ld] matrix.
+struct SketchPlan {
+  bool fast;
+  int ch, rc;            // tile: channels x sketch columns
+  int n_cslab, n_js, G;  // channel slabs, column slices, token splits
+  int tokens_per_split;
+};
+
+SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, int64_t ld) {
+  SketchPlan sp{};
+  sp.fast = d->io_dtype == ACC_BF16 && d->r % 64 == 0 && n * ld * 2 <= kMaxOperandBytes;
+  if (!sp.fast) {
+    sp.G = generic_sketch_splits(n, channels, d->r);
+    return sp;
+  }
+  if (d->r % 128 == 0) { sp.ch = 512; sp.rc = 128; } else { sp.ch = 1024; sp.rc = 64; }
+  sp.n_cslab = (int)ceil_div(channels, sp.ch);
+  sp.n_js = (int)(d->r / sp.rc);
+  int64_t G = (256 + sp.n_cslab * sp.n_js / 2) / (sp.n_cslab * sp.n_js);
+  const int64_t max_by_tokens = ceil_div(n, 256);
+  if (G > max_by_tokens) G = max_by_tokens;
+  if (G > 32) G = 32;
+  if (G < 1) G = 1;
+  sp.tokens_per_split = (int)round_up(ceil_div(n, G), 32);
+  sp.G = (int)ceil_div(n, sp.tokens_per_split);
+  if ((int64_t)sp.tokens_per_split * ld * 2 + 64 * ld * 2 > kMaxOperandBytes) sp.fast = false;
+  if (!sp.fast) sp.G = generic_sketch_splits(n, channels, d->r);
+  return sp;
+}
+
+// partial[g] (final orientation) with the tuned kernel, then K4 into `out`.
+void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, int64_t lda, int64_t channels,
+                 int64_t n, bool transposed, void* out, float* ws, Launcher& L) {
+  SketchFastParams p{};
+  p.A = (const bf16*)A; p.part = ws; p.n = n; p.C = channels; p.lda = lda; p.r = (int)d->r;
+  p.tokens_per_split = sp.tokens_per_split; p.n_cslab = sp.n_cslab; p.n_js = sp.n_js; p.G = sp.G;
+  p.sk = make_sketch_params(d);
+  const int pairs = sp.n_cslab * sp.G;
+  const dim3 grid((unsigned)(8 * sp.n_js * ceil_div(pairs, 8)));
+  if (sp.rc == 128) {
+    const size_t lds = sketch_bf16_lds_bytes<1, 4, 16>();
+    if (transposed) L.launch_lds(sketch_bf16_kernel<1, 4, 16, true, 0>, grid, dim3(256), lds, p);
+    else L.launch_lds(sketch_bf16_kernel<1, 4, 16, false, 0>, grid, dim3(256), lds, p);
+  } else {
+    const size_t lds = sketch_bf16_lds_bytes<2, 2, 16>();
+    if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true, 0>, grid, dim3(256), lds, p);
+    else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false, 0>, grid, dim3(256), lds, p);
+  }
+  const int64_t count = channels * d->r;
+  const unsigned blocks = (unsigned)ceil_div(count, 1024);
+  if (d->factor_dtype == ACC_BF16)
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), (const float*)ws, sp.G, count, count, (bf16*)out);
+  else
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, sp.G, count, count, (float*)out);
+}
+
+void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
+                bool transposed, void* out, float* ws, Launcher& L) {
+  const SketchPlan sp = plan_sketch(d, n, channels, lda);
+  if (sp.fast) fast_sketch(d, sp, A, lda, channels, n, transposed, out, ws, L);
+  else if (transposed) generic_sketch(d, A, lda, channels, n, 1, channels, out, ws, L);
+  else generic_sketch(d, A, lda, channels, n, d->r, 1, out, ws, L);
+}
+
 size_t workspace_bytes(const acc_linear_desc* d, const Shape& s, bool backward) {
   const int64_t channels = backward ? s.d_out : s.d_in;
-  const int G = generic_sketch_splits(s.n, channels, s.r);
-  return (size_t)G * (size_t)channels * (size_t)s.r * sizeof(float);
+  const SketchPlan sp = plan_sketch(d, s.n, channels, backward ? s.ldy : s.ldx);
+  return (size_t)sp.G * (size_t)channels * (size_t)s.r * sizeof(float);
 }
 
 }  // namespace
@@ -187,13 +289,17 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
 
-  GemmParams p{};
-  p.A = X; p.B = W; p.C = Y;
-  p.M = s.n; p.N = s.d_out; p.K = s.d_in;
-  p.a_sm = s.ldx; p.a_sk = 1; p.b_sk = s.ldw; p.b_sn = 1; p.c_sm = s.ldy; p.c_sn = 1;
-  p.k_per_split = round_up(s.d_in, 32);
-  generic_gemm_io(desc->io_dtype, p, L);
-  if (sketch) generic_sketch(desc, X, s.ldx, s.d_in, s.n, s.r, 1, Xs, (float*)workspace, L);
+  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
+    fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+  } else {
+    GemmParams p{};
+    p.A = X; p.B = W; p.C = Y;
+    p.M = s.n; p.N = s.d_out; p.K = s.d_in;
+    p.a_sm = s.ldx; p.a_sk = 1; p.b_sk = s.ldw; p.b_sn = 1; p.c_sm = s.ldy; p.c_sn = 1;
+    p.k_per_split = round_up(s.d_in, 32);
+    generic_gemm_io(desc->io_dtype, p, L);
+  }
+  if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L);
   return L.status();
 }
 
@@ -211,15 +317,26 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
 
-  GemmParams p{};
-  p.A = dY; p.B = W; p.C = dX;
-  p.M = s.n; p.N = s.d_in; p.K = s.d_out;
-  p.a_sm = s.ldy; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.ldw; p.c_sm = s.ldx; p.c_sn = 1;
-  p.k_per_split = round_up(s.d_out, 32);
-  generic_gemm_io(desc->io_dtype, p, L);
+  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
+    fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);  // W is [N = d_in, K = d_out]
+  } else {
+    GemmParams p{};
+    p.A = dY; p.B = W; p.C = dX;
+    p.M = s.n; p.N = s.d_in; p.K = s.d_out;
+    p.a_sm = s.ldy; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.ldw; p.c_sm = s.ldx; p.c_sn = 1;
+    p.k_per_split = round_up(s.d_out, 32);
+    generic_gemm_io(desc->io_dtype, p, L);
+  }
   // Gr[j, c] = sum_i S[i, j] dY[i, c]: the contraction of dY^T with S, stored transposed.
-  generic_sketch(desc, dY, s.ldy, s.d_out, s.n, 1, s.d_out, Gr, (float*)workspace, L);
-  if (dW) generic_dw(desc, s, Xs, Gr, dW, L);
+  run_sketch(desc, dY, s.ldy, s.d_out, s.n, true, Gr, (float*)workspace, L);
+  if (dW) {
+    if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
+      if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
+      else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
+    } else {
+      generic_dw(desc, s, Xs, Gr, dW, L);
+    }
+  }
   return L.status();
 }
 

@@ -47,30 +47,42 @@ __device__ __forceinline__ bf16x8 lds_read_b128(const char* lds, int byte_off) {
   return *(const bf16x8*)(lds + byte_off);
 }
 
-// 4 x 16 transposed read: the 16 lanes of a group give 4 rows x 4 chunks of 4 elements; lane l of the
-// group receives element l of each of the 4 rows.
+// 4 x 16 transposed read (ds_read_b64_tr_b16): the 16 lanes of a group give 4 rows x 4 chunks of 4
+// elements; lane l of the group receives element l of each of the 4 rows.
 __device__ __forceinline__ s16x4 lds_read_tr16_b64(const char* lds, int byte_off) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
       (s16x4 __attribute__((address_space(3)))*)(uintptr_t)(uint32_t)(uintptr_t)(lds + byte_off));
 }
 
 // Buffer resource over [base, base + bytes): loads beyond `bytes` return zero instead of faulting.
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, int64_t bytes) {
+__device__ __forceinline__ u32x4 make_rsrc(const void* base, int64_t bytes) {
   const uint32_t n = bytes > 0xFFFFFFFFll ? 0xFFFFFFFFu : (bytes < 0 ? 0u : (uint32_t)bytes);
-  return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, n, 0x00020000);  // raw buffer, 32-bit format
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  u32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xFFFFu);  // 48-bit base, stride 0
+  r[2] = __builtin_amdgcn_readfirstlane(n);                              // num_records in bytes
+  r[3] = 0x00020000u;                                                    // raw buffer, 32-bit data format
+  return r;
 }
 
 // 64 lanes x 16 bytes, global -> LDS without passing through registers (buffer_load_dwordx4 ... lds).
-// Lane i reads rsrc[voffset_i + soffset] and lands at lds_wave_base + 16 * i (lds_wave_base and
-// soffset wave-uniform); counted by vmcnt.
-__device__ __forceinline__ void buffer_to_lds_b128(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset,
-                                                   uint32_t soffset, char* lds_wave_base) {
-  __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)lds_wave_base, 16,
-                                           voffset, soffset, 0, 0);
+// Lane i reads rsrc[voffset_i + soffset] and lands at LDS byte (lds_wave_base + 16 * i); lds_wave_base
+// and soffset are wave-uniform.  Counted by vmcnt.
+// Written as inline assembly on purpose: when the compiler sees LDS-DMA it puts s_waitcnt vmcnt(0) in
+// front of every LDS read it cannot prove disjoint (all transposing reads), which serialises the
+// pipeline.  The caller therefore orders these transfers itself: wait_vmcnt0() + barrier before any
+// read of the destination stage.
+__device__ __forceinline__ void buffer_to_lds_b128(u32x4 rsrc, uint32_t voffset, uint32_t soffset,
+                                                   uint32_t lds_wave_base) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
+               :
+               : "v"(voffset), "s"(rsrc), "s"(soffset), "{m0}"(lds_wave_base)  // M0 = LDS destination
+               : "memory");
 }
 
 // s_waitcnt vmcnt(0) (expcnt / lgkmcnt untouched): all global -> LDS transfers of this wave landed.
-__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0f70); }
+__device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Map the linear work-group id to an output tile so that the 32 tiles resident on one XCD
 // (work-groups are dealt round-robin to the 8 XCDs) form a super_m x super_n block that shares
@@ -113,8 +125,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   // buffer resources that start at the tile's first row / column; rows past the end of the matrix
   // read as zero (their products are never stored).
   const int64_t am0 = DBG == 7 ? 0 : m0, bn0 = DBG == 7 ? 0 : n0;
-  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(p.A + am0 * p.lda, ((p.M - am0 - 1) * p.lda + p.K) * 2);
-  const __amdgpu_buffer_rsrc_t b_rsrc =
+  const u32x4 a_rsrc = make_rsrc(p.A + am0 * p.lda, ((p.M - am0 - 1) * p.lda + p.K) * 2);
+  const u32x4 b_rsrc =
       B_KMAJOR ? make_rsrc(p.B + bn0 * p.ldb, ((p.N - bn0 - 1) * p.ldb + p.K) * 2)
                : make_rsrc(p.B + bn0, ((p.K - 1) * p.ldb + (p.N - bn0)) * 2);
   uint32_t a_src[A_LOADS];
@@ -140,7 +152,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   }
   const uint32_t b_kstep = B_KMAJOR ? BK * 2 : (uint32_t)(BK * p.ldb * 2);  // bytes per K tile
 
-  auto issue_loads = [&](int kt, char* stage) {
+  auto issue_loads = [&](int kt, uint32_t stage) {
 #pragma unroll
     for (int t = 0; t < A_LOADS; ++t)
       buffer_to_lds_b128(a_rsrc, a_src[t], (uint32_t)kt * (BK * 2), stage + (t * NW + wave) * 1024);
@@ -172,25 +184,6 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
     }
   }
   const int a_swz = swz(lrow);  // rows i * 32 + lrow share swz(lrow)
-
-  auto load_a = [&](const char* cur, int s, bf16x8(&af)[TM], bool force = false) {
-    if (DBG == 5 && !force) return;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) af[i] = lds_read_b128(cur, a_rd[i] + (((2 * s + kg) ^ a_swz) << 4));
-  };
-  auto load_b = [&](const char* cur, int s, bf16x8(&bfr)[TN], bool force = false) {
-    if (DBG == 5 && !force) return;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      if (B_KMAJOR) {
-        bfr[j] = lds_read_b128(cur, b_rd[j][0] + (((2 * s + kg) ^ a_swz) << 4));
-      } else {
-        const s16x4 lo = lds_read_tr16_b64(cur, b_rd[j][0] + 16 * s * (BN * 2));
-        const s16x4 hi = lds_read_tr16_b64(cur, b_rd[j][1] + 16 * s * (BN * 2));
-        bfr[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-      }
-    }
-  };
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -225,7 +218,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
       dst[j] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
   };
-  auto issue_one = [&](int g, int kt, char* stage) {  // g-th wave-load of a K tile (A first, then B)
+  auto issue_one = [&](int g, int kt, uint32_t stage) {  // g-th wave-load of a K tile (A first, then B)
     if (g < A_LOADS) buffer_to_lds_b128(a_rsrc, a_src[g], (uint32_t)kt * (BK * 2), stage + (g * NW + wave) * 1024);
     else buffer_to_lds_b128(b_rsrc, b_src[g - A_LOADS], (uint32_t)kt * b_kstep,
                             stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024);
@@ -241,7 +234,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   constexpr int G_PER_STEP = (NG_TOTAL + G_STEPS - 1) / G_STEPS;
   constexpr int G_EVERY = NM / G_PER_STEP > 0 ? NM / G_PER_STEP : 1;
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s,
-                   bf16x8(&na)[TM], bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, char* nxt) {
+                   bf16x8(&na)[TM], bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, uint32_t nxt) {
 #pragma unroll
     for (int q = 0; q < NM; ++q) {
       const int i = q / TN, j = q % TN;
@@ -260,7 +253,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   };
 
   // prologue: tile 0 -> stage 0, operands of its first k-step -> registers
-  issue_loads(0, smem);
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;  // LDS byte address of the dynamic segment
+  issue_loads(0, smem_lds);
   wait_vmcnt0();
   __syncthreads();
 #pragma unroll
@@ -276,20 +270,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
 
   for (int kt = 0; kt < KT; ++kt) {
     const char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    const char* nxt = smem + ((kt + 1) & 1) * STAGE;
+    const uint32_t nxt_lds = smem_lds + ((kt + 1) & 1) * STAGE;
     // Branch-free body: the last iteration re-loads its own tile into the idle stage, unused.
     const int kt_next = kt + 1 < KT ? kt + 1 : kt;
     __builtin_amdgcn_sched_barrier(0);
-    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt);
+    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
     // The next tile must have landed (every wave's transfers) before anyone reads it, and every
     // wave must be done reading `cur` before the tile after next is written over it.
     wait_vmcnt0();
     if (DBG != 6) __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     // last k-step of this tile covers the latency of the first operand reads of the next one
-    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt);
+    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt_lds);
   }
 
   // ---- epilogue: lane holds column (lane & 31), rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4 ----

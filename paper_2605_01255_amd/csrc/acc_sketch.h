@@ -1,0 +1,188 @@
+// Tuned bf16 sketch kernel for gfx950 (steps F0 + F2 and F0 + B2):
+//
+//   part[g][c][j] = sum over the tokens t of split g of  A[t, c] * S[t, j]          (TRANSPOSED = false, Xs)
+//   part[g][j][c] = the same value stored transposed                                 (TRANSPOSED = true,  Gr)
+//
+// A is X [n, d_in] or dY [n, d_out] (row-major, channels contiguous); S[t, j] is regenerated from the
+// Philox counter (token, column) in registers, directly in MFMA operand layout, and never stored.
+//
+// Work-group = WC x WJ waves; output tile (WC * CWB * 32) channels x (WJ * 32) sketch columns, fp32
+// accumulators in registers for the whole token range of the split (CWB * 16 registers per lane).
+// Tokens stream through LDS in stages of 32 rows (global -> LDS directly, double buffered); the
+// channel-major MFMA operand is formed from the token-major tile with transposing LDS reads.
+// The contraction runs over tokens, so one Philox call (4 tokens of one column) feeds half an
+// operand register set; every wave generates only the 32 columns it multiplies.
+#pragma once
+#include "acc_common.h"
+#include "acc_gemm.h"
+#include "acc_rng.h"
+
+namespace acc {
+
+struct SketchFastParams {
+  const bf16* A;       // [n, lda]
+  float* part;         // [G][C][r] or [G][r][C]
+  int64_t n, C, lda;
+  int r;
+  int tokens_per_split;  // multiple of 32
+  int n_cslab, n_js, G;  // channel slabs, column slices, token splits
+  SketchParams sk;
+};
+
+template <int WC, int WJ, int CWB, bool TRANSPOSED, int DBG = 0>
+__global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastParams p) {
+  constexpr int NW = WC * WJ;
+  constexpr int CH = WC * CWB * 32, RC = WJ * 32, BT = 32;
+  constexpr int ROW_BYTES = CH * 2;
+  constexpr int STAGE = BT * ROW_BYTES;
+  constexpr int PARTS = ROW_BYTES / 1024;       // 1 KB wave-loads per token row
+  constexpr int LOADS = BT * PARTS / NW;        // wave-loads per wave and stage
+  static_assert(BT * PARTS % NW == 0, "stage/waves");
+  static_assert(CH % 512 == 0, "channel slab must be a multiple of 512");
+  static_assert(CWB % 4 == 0, "the row swizzle permutes groups of four 32-channel blocks");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  // ---- which tile: pairs of column slices of one (split, slab) share an XCD (blockIdx % 8) ----
+  const int b = blockIdx.x;
+  const int js = (b >> 3) % p.n_js;
+  const int pair = (b & 7) + 8 * ((b >> 3) / p.n_js);
+  if (pair >= p.n_cslab * p.G) return;
+  const int slab = pair % p.n_cslab, g = pair / p.n_cslab;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wc = wave / WJ, wj = wave % WJ;
+  const int64_t t_begin = (int64_t)g * p.tokens_per_split;
+  const int64_t c0 = (int64_t)slab * CH;
+  int64_t t_end = t_begin + p.tokens_per_split;
+  if (t_end > p.n) t_end = p.n;
+  const int NS = t_end > t_begin ? (int)((t_end - t_begin + BT - 1) / BT) : 0;
+
+  // ---- global -> LDS: wave-load L = t * NW + wave covers token row L / PARTS, kilobyte L % PARTS ----
+  const u32x4 rsrc = make_rsrc(p.A + t_begin * p.lda + c0, ((p.n - t_begin - 1) * p.lda + (p.C - c0)) * 2);
+  uint32_t src[LOADS];
+  uint32_t dst[LOADS];
+#pragma unroll
+  for (int t = 0; t < LOADS; ++t) {
+    const int L = t * NW + wave, row = L / PARTS, part = L % PARTS;
+    const int chunk = (part * 64 + lane) ^ swz_n(row);   // 16-byte chunk of the row this lane fetches
+    src[t] = (uint32_t)(row * p.lda * 2 + chunk * 16);
+    dst[t] = (uint32_t)(row * ROW_BYTES + part * 1024);
+  }
+  const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
+  auto issue_stage = [&](int st, uint32_t stage_lds) {
+    const uint32_t soff = (uint32_t)st * (uint32_t)(BT * p.lda * 2);
+#pragma unroll
+    for (int t = 0; t < LOADS; ++t) buffer_to_lds_b128(rsrc, src[t], soff, stage_lds + dst[t]);
+  };
+
+  // ---- LDS addresses of the transposing operand reads ----
+  // 16-lane group gq = lane / 16 reads channels 16 * (gq & 1) .. and tokens 8 * (gq >> 1) ..; lane i of
+  // the group reads token i / 4 (+ 4 for the second half), 4-channel chunk i % 4.  The row swizzle only
+  // touches bits 2..3 of the 16-byte chunk index, i.e. the 32-channel block index modulo 4.
+  const int gq = lane >> 4, i16 = lane & 15;
+  const int xr = (i16 >> 2) & 3;
+  int rd_base[4];
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int row = 8 * (gq >> 1) + (i16 >> 2);
+    const int col16 = 2 * (gq & 1) + ((i16 & 3) >> 1);  // 16-byte chunk within the 32-channel block
+    rd_base[v] = row * ROW_BYTES + (((((wc * CWB) & 3) ^ v ^ xr) & 3) << 6) + (col16 << 4) + ((i16 & 1) << 3) +
+                 (((wc * CWB) >> 2) << 8);
+  }
+  // operand of channel block mb (0 .. CWB-1) of k-step s (0, 1) from stage `st`
+  auto read_block = [&](const char* st, int s, int mb) -> bf16x8 {
+    const int off = s * 16 * ROW_BYTES + (mb >> 2) * 256;
+    const s16x4 lo = lds_read_tr16_b64(st, rd_base[mb & 3] + off);
+    const s16x4 hi = lds_read_tr16_b64(st, rd_base[mb & 3] + off + 4 * ROW_BYTES);
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  // ---- S operand: lane holds column j, tokens 8 * (lane >> 5) .. + 7 of the k-step ----
+  const uint32_t jcol = (uint32_t)(js * RC + wj * 32 + (lane & 31));
+  const uint64_t q_lane = ((p.sk.row_offset + (uint64_t)t_begin) >> 2) + 2 * (uint64_t)(lane >> 5);
+  auto make_s = [&](int kstep) -> bf16x8 {  // kstep counts 16-token steps from t_begin
+    uint32_t w0[4], w1[4];
+    float z0[4], z1[4];
+    const uint64_t q = q_lane + 4 * (uint64_t)kstep;
+    sketch_words(p.sk.key0, p.sk.key1, q, jcol, w0);
+    sketch_words(p.sk.key0, p.sk.key1, q + 1, jcol, w1);
+    normals_from_words<false>(w0, p.sk.inv_sqrt_r, p.sk.neg2_ln2_over_r, z0);
+    normals_from_words<false>(w1, p.sk.inv_sqrt_r, p.sk.neg2_ln2_over_r, z1);
+    bf16x8 s;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      s[t] = (bf16)z0[t];
+      s[4 + t] = (bf16)z1[t];
+    }
+    return s;
+  };
+
+  f32x16 acc[CWB];
+#pragma unroll
+  for (int i = 0; i < CWB; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+  auto multiply = [&](const char* st, int s, bf16x8 sf) {
+    bf16x8 a = read_block(st, s, 0);
+#pragma unroll
+    for (int mb = 0; mb < CWB; ++mb) {
+      bf16x8 nxt = a;
+      if (mb + 1 < CWB) nxt = read_block(st, s, mb + 1);
+      if (DBG != 2) {
+        if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, a, acc[mb], 0, 0, 0);
+        else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, sf, acc[mb], 0, 0, 0);
+      } else {
+        acc[mb][0] += (float)a[0] * (float)sf[0];
+      }
+      a = nxt;
+    }
+  };
+
+  if (NS > 0) {
+    issue_stage(0, smem_lds);
+    bf16x8 s_cur = make_s(0);
+    wait_vmcnt0();
+    __syncthreads();
+    for (int st = 0; st < NS; ++st) {
+      const char* cur = smem + (st & 1) * STAGE;
+      const int st_next = st + 1 < NS ? st + 1 : st;  // branch-free: the last stage is fetched twice
+      issue_stage(st_next, smem_lds + ((st + 1) & 1) * STAGE);
+      const bf16x8 s_mid = make_s(2 * st + 1);        // generated while k-step 0 is multiplied
+      multiply(cur, 0, s_cur);
+      s_cur = make_s(2 * st + 2);                     // first k-step of the next stage
+      multiply(cur, 1, s_mid);
+      wait_vmcnt0();
+      __syncthreads();
+    }
+  }
+
+  // ---- store the fp32 partial tile ----
+  // lane holds MFMA column (lane & 31) and rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4
+  float* __restrict__ out = p.part + (int64_t)g * p.C * p.r;
+  const int lcol = lane & 31, kg = lane >> 5;
+#pragma unroll
+  for (int mb = 0; mb < CWB; ++mb) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int rowi = (e >> 2) * 8 + kg * 4 + (e & 3);
+      if (!TRANSPOSED) {  // rows = channels, columns = sketch columns
+        const int64_t c = c0 + (wc * CWB + mb) * 32 + rowi;
+        const int64_t j = js * RC + wj * 32 + lcol;
+        if (c < p.C) out[c * p.r + j] = acc[mb][e];
+      } else {            // rows = sketch columns, columns = channels
+        const int64_t c = c0 + (wc * CWB + mb) * 32 + lcol;
+        const int64_t j = js * RC + wj * 32 + rowi;
+        if (c < p.C) out[j * p.C + c] = acc[mb][e];
+      }
+    }
+  }
+}
+
+template <int WC, int WJ, int CWB>
+constexpr int sketch_bf16_lds_bytes() {
+  return 2 * 32 * (WC * CWB * 32) * 2;
+}
+
+}  // namespace acc
