@@ -1,0 +1,80 @@
+"""GPU path vs oracle at the benchmark configurations' full sizes, in the launch configuration
+bench.py times: whole outputs where the oracle finishes in seconds (the 3B-shaped projection),
+otherwise on sampled rows / channels / columns the oracle computes one by one (fixed sample seed)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2605_01255_amd import inputs
+from oracle import acc_oracle as orc
+import gpu_util as gu
+
+
+@pytest.fixture(scope="module")
+def acc():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_01255_amd import binding
+    return binding
+
+
+def test_c2_full_outputs(acc):
+    """LLaMA-3B-shaped attention projection, every element of every output."""
+    lin = inputs.config("c2")[0]
+    data = inputs.make(lin)
+    got = gu.run_layer(acc, lin, data)
+    want = gu.run_oracle(lin, data)
+    errs = {k: gu.rel(got[k], want[k]) for k in want}
+    print(lin.name, " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= 1e-2 for v in errs.values()), errs
+    # the x20 outlier channels dominate ||Xs||: check them and the ordinary channels separately
+    out_ch = inputs.outlier_channels(lin.d_in, lin.n_outliers)
+    rest = np.setdiff1d(np.arange(lin.d_in), out_ch)
+    assert gu.rel(got["Xs"][out_ch], want["Xs"][out_ch]) <= 1e-2
+    assert gu.rel(got["Xs"][rest], want["Xs"][rest]) <= 1e-2
+    assert gu.rel(got["dW"][rest], want["dW"][rest]) <= 1e-2
+
+
+def _sampled_check(acc, lin, rng):
+    data = inputs.make(lin)
+    got = gu.run_layer(acc, lin, data)
+    X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+    S = orc.sketch_matrix(lin.seed, lin.n, lin.r)
+    rows = np.sort(rng.choice(lin.n, size=min(256, lin.n), replace=False))
+    chs = np.sort(rng.choice(lin.d_in, size=64, replace=False))
+    cols = np.sort(rng.choice(lin.d_out, size=64, replace=False))
+    Y_rows, _ = orc.linear_fwd(X[rows], W, S=S[rows])
+    dX_rows, _, _ = orc.linear_bwd(dY[rows], W, np.zeros((lin.d_in, lin.r)), S=S[rows], want_dW=False)
+    _, Xs_ch = orc.linear_fwd(X[:, chs], W[chs][:, :8], S=S)                       # [64, r]
+    _, Gr_cols, dW_blk = orc.linear_bwd(dY[:, cols], W[:8][:, cols], Xs_ch, S=S)   # [r, 64], [64, 64]
+    errs = {"Y": gu.rel(got["Y"][rows], Y_rows), "dX": gu.rel(got["dX"][rows], dX_rows),
+            "Xs": gu.rel(got["Xs"][chs], Xs_ch), "Gr": gu.rel(got["Gr"][:, cols], Gr_cols),
+            "dW": gu.rel(got["dW"][np.ix_(chs, cols)], dW_blk)}
+    print(lin.name, f"r={lin.r}", " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= 1e-2 for v in errs.values()), (lin.name, errs)
+    # invariants that hold at any size: S^T S structure shows up as ||Gr||^2 ~ ||dY||^2 (1/r per column pair)
+    ratio = np.sum(got["Gr"] ** 2) / np.sum(dY ** 2)
+    assert 0.9 < ratio < 1.1, ratio
+
+
+@pytest.mark.parametrize("name", ["c4.k", "c4.gate", "c4.down"])
+def test_c4_linears_sampled(acc, name):
+    """Decoder-layer linears of the 3B shape (k/v 3072->1024, gate/up 3072->8192, down 8192->3072)."""
+    lin = [l for l in inputs.config("c4") if l.name == name][0]
+    _sampled_check(acc, lin, np.random.default_rng(1))
+
+
+@pytest.mark.parametrize("r", [64, 128, 512])
+def test_c3_down_ranks_sampled(acc, r):
+    """MLP down-projection (SwiGLU input) at the other ranks of the rank sweep."""
+    lin = [l for l in inputs.config(f"c3_r{r}") if l.name == "c3.down"][0]
+    _sampled_check(acc, lin, np.random.default_rng(2))
+
+
+@pytest.mark.parametrize("name", ["c5.q", "c5.k"])
+def test_c5_linears_sampled(acc, name):
+    """8B-shaped layer, n = 65536 tokens, r = 512, low-rank-plus-noise activations."""
+    lin = [l for l in inputs.config("c5") if l.name == name][0]
+    _sampled_check(acc, lin, np.random.default_rng(3))

@@ -132,3 +132,23 @@ def test_factored_gradient_is_unbiased_on_gpu(acc):
             err = np.linalg.norm(total.cpu().numpy() / (seed + 1) - dense)
             assert 0.9 < err / np.sqrt(cf / (seed + 1)) < 1.1, (seed + 1, err)
     assert abs(sq / 50 / cf - 1.0) < 0.05
+
+
+FAST_SHAPES = [
+    # shapes the tuned bf16 kernels take (K % 64 == 0, r % 64 == 0) with ragged token / column tails
+    (1000, 512, 640, 128),      # 128x128 tiles, ragged M
+    (4100, 1024, 3080, 256),    # 256x256 tiles, ragged M and N
+    (2500, 576, 1096, 64),      # rank-64 sketch tile, ragged channel slab (576 < 1024)
+    (8192, 2048, 2048, 192),    # r % 64 == 0 but r % 128 != 0
+    (33, 64, 64, 64),           # a single partial stage
+]
+
+
+@pytest.mark.parametrize("n,d_in,d_out,r", FAST_SHAPES)
+def test_bf16_tuned_kernel_shapes(acc, n, d_in, d_out, r):
+    _check(acc, inputs.Linear(f"fast_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16"))
+
+
+def test_tuned_kernels_fp32_dw_and_strides(acc):
+    lin = inputs.Linear("fast_strided", 1500, 512, 768, 128, dtype="bf16")
+    _check(acc, lin, dw_dtype=0, pad=(64, 8, 72), row_offset=4 * 77, seed=0xABCDEF0123)
