@@ -27,14 +27,35 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+__device__ __forceinline__ float uniform_from_word(uint32_t x) {
+  return ((float)(x >> 9) + 0.5f) * 0x1p-23f;  // every step exact in fp32
+}
+
+// One Philox4x32 round on a counter held in c[0..3]; round_index selects the bumped key (wave-uniform).
+__device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t key0, uint32_t key1, int round_index) {
+  const uint32_t k0 = key0 + (uint32_t)round_index * 0x9E3779B9u;
+  const uint32_t k1 = key1 + (uint32_t)round_index * 0xBB67AE85u;
+  const uint64_t p0 = (uint64_t)0xD2511F53u * c[0];
+  const uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
+  const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
+  const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
+  const uint32_t n0 = hi1 ^ c[1] ^ k0, n2 = hi0 ^ c[3] ^ k1;
+  c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
+}
+
+// One Box-Muller pair from two words (fast hardware generator, already scaled by 1/sqrt(r)).
+__device__ __forceinline__ void box_muller_fast(uint32_t wa, uint32_t wb, float neg2_ln2_over_r, float& z_even,
+                                                float& z_odd) {
+  const float u1 = uniform_from_word(wa), u2 = uniform_from_word(wb);
+  const float radius = __builtin_amdgcn_sqrtf(neg2_ln2_over_r * __builtin_amdgcn_logf(u1));
+  z_even = radius * __builtin_amdgcn_cosf(u2);
+  z_odd = radius * __builtin_amdgcn_sinf(u2);
+}
+
 // The four Philox words of token group g4 = (global token >> 2) and column j.
 __device__ __forceinline__ void sketch_words(uint32_t key0, uint32_t key1, uint64_t g4, uint32_t j,
                                              uint32_t (&w)[4]) {
   philox4x32_10((uint32_t)g4, j, 0u, (uint32_t)(g4 >> 32), key0, key1, w);
-}
-
-__device__ __forceinline__ float uniform_from_word(uint32_t x) {
-  return ((float)(x >> 9) + 0.5f) * 0x1p-23f;  // every step exact in fp32
 }
 
 // Four entries of S (tokens 4*g4 .. 4*g4+3 of one column), already scaled by 1/sqrt(r).

@@ -8,8 +8,10 @@
 //
 // Work-group = WC x WJ waves; output tile (WC * CWB * 32) channels x (WJ * 32) sketch columns, fp32
 // accumulators in registers for the whole token range of the split (CWB * 16 registers per lane).
-// Tokens stream through LDS in stages of 32 rows (global -> LDS directly, double buffered); the
-// channel-major MFMA operand is formed from the token-major tile with transposing LDS reads.
+// Tokens stream through LDS in stages of 16 rows (one MFMA k-step), global -> LDS directly, in a ring of
+// NSTAGE stages with NSTAGE - 1 stages in flight: the input is read once from HBM, so enough bytes
+// must be outstanding per CU to cover DRAM latency.  The channel-major MFMA operand is formed from
+// the token-major tile with transposing LDS reads.
 // The contraction runs over tokens, so one Philox call (4 tokens of one column) feeds half an
 // operand register set; every wave generates only the 32 columns it multiplies.
 #pragma once
@@ -32,9 +34,11 @@ struct SketchFastParams {
 template <int WC, int WJ, int CWB, bool TRANSPOSED, int DBG = 0>
 __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastParams p) {
   constexpr int NW = WC * WJ;
-  constexpr int CH = WC * CWB * 32, RC = WJ * 32, BT = 32;
+  constexpr int CH = WC * CWB * 32, RC = WJ * 32, BT = 16;
   constexpr int ROW_BYTES = CH * 2;
   constexpr int STAGE = BT * ROW_BYTES;
+  constexpr int NSTAGE = 128 * 1024 / STAGE;    // ring of stages in 128 KB of LDS
+  constexpr int DEPTH = NSTAGE - 1;             // stages in flight
   constexpr int PARTS = ROW_BYTES / 1024;       // 1 KB wave-loads per token row
   constexpr int LOADS = BT * PARTS / NW;        // wave-loads per wave and stage
   static_assert(BT * PARTS % NW == 0, "stage/waves");
@@ -56,7 +60,7 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   const int64_t c0 = (int64_t)slab * CH;
   int64_t t_end = t_begin + p.tokens_per_split;
   if (t_end > p.n) t_end = p.n;
-  const int NS = t_end > t_begin ? (int)((t_end - t_begin + BT - 1) / BT) : 0;
+  const int NS = t_end > t_begin ? (int)((t_end - t_begin + BT - 1) / BT) : 0;  // stages = k-steps
 
   // ---- global -> LDS: wave-load L = t * NW + wave covers token row L / PARTS, kilobyte L % PARTS ----
   const u32x4 rsrc = make_rsrc(p.A + t_begin * p.lda + c0, ((p.n - t_begin - 1) * p.lda + (p.C - c0)) * 2);
@@ -90,9 +94,9 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
     rd_base[v] = row * ROW_BYTES + (((((wc * CWB) & 3) ^ v ^ xr) & 3) << 6) + (col16 << 4) + ((i16 & 1) << 3) +
                  (((wc * CWB) >> 2) << 8);
   }
-  // operand of channel block mb (0 .. CWB-1) of k-step s (0, 1) from stage `st`
-  auto read_block = [&](const char* st, int s, int mb) -> bf16x8 {
-    const int off = s * 16 * ROW_BYTES + (mb >> 2) * 256;
+  // operand of channel block mb (0 .. CWB-1) from stage `st`
+  auto read_block = [&](const char* st, int mb) -> bf16x8 {
+    const int off = (mb >> 2) * 256;
     const s16x4 lo = lds_read_tr16_b64(st, rd_base[mb & 3] + off);
     const s16x4 hi = lds_read_tr16_b64(st, rd_base[mb & 3] + off + 4 * ROW_BYTES);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   // ---- S operand: lane holds column j, tokens 8 * (lane >> 5) .. + 7 of the k-step ----
   const uint32_t jcol = (uint32_t)(js * RC + wj * 32 + (lane & 31));
   const uint64_t q_lane = ((p.sk.row_offset + (uint64_t)t_begin) >> 2) + 2 * (uint64_t)(lane >> 5);
-  auto make_s = [&](int kstep) -> bf16x8 {  // kstep counts 16-token steps from t_begin
+  auto make_s = [&](int kstep) -> bf16x8 {  // kstep counts 16-token steps from t_begin (prologue only)
     uint32_t w0[4], w1[4];
     float z0[4], z1[4];
     const uint64_t q = q_lane + 4 * (uint64_t)kstep;
@@ -124,39 +128,85 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
-  auto multiply = [&](const char* st, int s, bf16x8 sf) {
-    bf16x8 a = read_block(st, s, 0);
+  // One k-step (16 tokens) in CWB slots.  Slot mb issues MFMA mb on operands already in registers, the
+  // two transposing reads of operand mb of the following k-step, and one slice of the generation of
+  // the S operand of the following k-step (10 Philox rounds on two counters, 4 Box-Muller pairs, pack).
+  // Fences between slots keep this order: the matrix pipe and the vector ALU then run concurrently
+  // instead of one after the other, and every LDS read has a whole k-step to return.
+  static_assert(CWB >= 16, "the S generation is spread over 16 slots");
+  struct SGen {
+    uint32_t c[2][4];
+    float z[8];
+  };
+  auto sgen_slot = [&](SGen& g, int slot, int kstep, bf16x8& out) {
+    if (slot == 0) {
+      const uint64_t q = q_lane + 4 * (uint64_t)kstep;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        g.c[h][0] = (uint32_t)(q + h); g.c[h][1] = jcol; g.c[h][2] = 0u; g.c[h][3] = (uint32_t)((q + h) >> 32);
+      }
+    }
+    if (slot < 10) {
+      philox_round(g.c[0], p.sk.key0, p.sk.key1, slot);
+      philox_round(g.c[1], p.sk.key0, p.sk.key1, slot);
+    } else if (slot < 14) {
+      const int pr = slot - 10, h = pr >> 1, a = (pr & 1) * 2;
+      box_muller_fast(g.c[h][a], g.c[h][a + 1], p.sk.neg2_ln2_over_r, g.z[4 * h + a], g.z[4 * h + a + 1]);
+    } else if (slot == 14) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
+    }
+  };
+  auto kstep_slots = [&](const bf16x8(&af)[CWB], bf16x8 sf, const char* rd_stage, bf16x8(&nf)[CWB], SGen& g,
+                         int gen_kstep, bf16x8& s_next) {
 #pragma unroll
     for (int mb = 0; mb < CWB; ++mb) {
-      bf16x8 nxt = a;
-      if (mb + 1 < CWB) nxt = read_block(st, s, mb + 1);
       if (DBG != 2) {
-        if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, a, acc[mb], 0, 0, 0);
-        else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, sf, acc[mb], 0, 0, 0);
+        if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, af[mb], acc[mb], 0, 0, 0);
+        else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], sf, acc[mb], 0, 0, 0);
       } else {
-        acc[mb][0] += (float)a[0] * (float)sf[0];
+        acc[mb][0] += (float)af[mb][0] * (float)sf[0];
       }
-      a = nxt;
+      nf[mb] = read_block(rd_stage, mb);
+      sgen_slot(g, mb, gen_kstep, s_next);
+      __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // s_waitcnt vmcnt((DEPTH - 1) * LOADS): everything but the DEPTH - 1 youngest stages has landed
+  auto wait_oldest_stage = [&]() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LOADS) : "memory");
+  };
+  // One iteration = one k-step t: start the transfer of stage t + DEPTH into the slot stage t - 1 used,
+  // make sure stage t + 1 has landed for every wave, then multiply k-step t while reading t + 1.
+  // Branch-free: past the end the last stage is fetched again into a slot nobody reads.
+  auto iteration = [&](int t, const bf16x8(&af)[CWB], bf16x8 sf, bf16x8(&nf)[CWB], SGen& g, bf16x8& s_next) {
+    const int t_load = t + DEPTH < NS ? t + DEPTH : NS - 1;
+    __builtin_amdgcn_sched_barrier(0);
+    issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
+    wait_oldest_stage();
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    kstep_slots(af, sf, smem + ((t + 1) % NSTAGE) * STAGE, nf, g, t + 1, s_next);
   };
 
   if (NS > 0) {
-    issue_stage(0, smem_lds);
-    bf16x8 s_cur = make_s(0);
-    wait_vmcnt0();
+    bf16x8 fa[CWB], fb[CWB];
+    SGen gen;
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue_stage(d < NS ? d : NS - 1, smem_lds + d * STAGE);
+    bf16x8 s_a = make_s(0), s_b = s_a;
+    wait_oldest_stage();
     __syncthreads();
-    for (int st = 0; st < NS; ++st) {
-      const char* cur = smem + (st & 1) * STAGE;
-      const int st_next = st + 1 < NS ? st + 1 : st;  // branch-free: the last stage is fetched twice
-      issue_stage(st_next, smem_lds + ((st + 1) & 1) * STAGE);
-      const bf16x8 s_mid = make_s(2 * st + 1);        // generated while k-step 0 is multiplied
-      multiply(cur, 0, s_cur);
-      s_cur = make_s(2 * st + 2);                     // first k-step of the next stage
-      multiply(cur, 1, s_mid);
-      wait_vmcnt0();
-      __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < CWB; ++mb) fa[mb] = read_block(smem, mb);
+    int t = 0;
+    for (; t + 1 < NS; t += 2) {
+      iteration(t, fa, s_a, fb, gen, s_b);
+      iteration(t + 1, fb, s_b, fa, gen, s_a);
     }
+    if (t < NS) iteration(t, fa, s_a, fb, gen, s_b);
   }
+  wait_vmcnt0();  // no transfer may still be in flight when the work-group's LDS is released
 
   // ---- store the fp32 partial tile ----
   // lane holds MFMA column (lane & 31) and rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4
@@ -182,7 +232,7 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
 
 template <int WC, int WJ, int CWB>
 constexpr int sketch_bf16_lds_bytes() {
-  return 2 * 32 * (WC * CWB * 32) * 2;
+  return 128 * 1024;
 }
 
 }  // namespace acc
