@@ -98,7 +98,7 @@ __device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int& tm, int& 
   return tm < p.tiles_m && tn < p.tiles_n;
 }
 
-template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0>
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0, int GS = 3>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   // while the texture path drains and starves the MFMA pipe.
   constexpr int NM = TM * TN;
   constexpr int NG_TOTAL = A_LOADS + B_LOADS;
-  constexpr int G_STEPS = 3;                                   // k-steps that carry wave-loads
+  constexpr int G_STEPS = GS;                                  // k-steps that carry wave-loads
   constexpr int G_PER_STEP = (NG_TOTAL + G_STEPS - 1) / G_STEPS;
   constexpr int G_EVERY = NM / G_PER_STEP > 0 ? NM / G_PER_STEP : 1;
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s,
@@ -238,7 +238,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
 #pragma unroll
     for (int q = 0; q < NM; ++q) {
       const int i = q / TN, j = q % TN;
-      if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ca[i], cb[j], acc[i][j], 0, 0, 0);
+      // B operand first: the product comes out transposed, lane = output row, 4 consecutive registers =
+      // 4 consecutive output columns, which is what the epilogue packs
+      if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
       else acc[i][j][0] += (float)ca[i][0] * (float)cb[j][0];
       if (DBG != 5 && DBG != 9) {
         if (q < TM) read_a1(rd_stage, rd_s, q, na);
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
     const int kt_next = kt + 1 < KT ? kt + 1 : kt;
     __builtin_amdgcn_sched_barrier(0);
     kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_STEPS > 1 ? G_PER_STEP : 0, kt_next, nxt_lds);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_STEPS > 2 ? G_PER_STEP : 0, kt_next, nxt_lds);
     // The next tile must have landed (every wave's transfers) before anyone reads it, and every
     // wave must be done reading `cur` before the tile after next is written over it.
     wait_vmcnt0();
@@ -287,20 +289,46 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
     kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt_lds);
   }
 
-  // ---- epilogue: lane holds column (lane & 31), rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4 ----
+  // ---- epilogue ----
+  // Lane holds output row (lane & 31) of each 32 x 32 block and columns 8 * (e / 4) + 4 * (lane >> 5) +
+  // e % 4.  Each wave stages 32 rows of its tile in a private, padded LDS region (8- or 16-byte writes,
+  // conflict-free), reads them back row-contiguous and stores 16 bytes per lane: full cache lines.
+  constexpr int ES = sizeof(TC);
+  constexpr int ROW_B = TN * 32 * ES;            // bytes of one staged row
+  constexpr int PITCH = ROW_B + 8;               // +2 banks per row: 32 rows land on distinct banks
+  constexpr int CH16 = ROW_B / 16;               // 16-byte chunks per row
+  constexpr int WAVE_B = 32 * PITCH;
+  static_assert(NW * WAVE_B <= 2 * STAGE, "epilogue staging exceeds the pipeline's LDS");
+  __syncthreads();                               // every wave is done with the pipeline's LDS
+  char* stage_w = smem + wave * WAVE_B;
   TC* __restrict__ C = (TC*)p.C;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int64_t gn = n0 + (wn * TN + j) * 32 + lrow;
-      if (gn < p.N) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int64_t gm = m0 + (wm * TM + i) * 32 + (e >> 2) * 8 + kg * 4 + (e & 3);
-          if (gm < p.M && ((DBG != 8 && DBG != 9) || acc[i][j][e] == 1234.5f)) C[gm * p.ldc + gn] = from_f32<TC>(acc[i][j][e]);
+      for (int g4 = 0; g4 < 4; ++g4) {
+        char* dst = stage_w + lrow * PITCH + (j * 32 + g4 * 8 + kg * 4) * ES;
+        if constexpr (ES == 2) {
+          bf16x4 v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = (bf16)acc[i][j][g4 * 4 + t];
+          *(bf16x4*)dst = v;
+        } else {
+          f32x4 v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][g4 * 4 + t];
+          *(f32x4*)dst = v;
         }
       }
+    }
+#pragma unroll
+    for (int t = 0; t < 32 * CH16 / 64; ++t) {
+      const int idx = t * 64 + lane, row = idx / CH16, ch = idx % CH16;
+      const u32x4 v = *(const u32x4*)(stage_w + row * PITCH + ch * 16);
+      const int64_t gm = m0 + (wm * TM + i) * 32 + row;
+      const int64_t gn = n0 + wn * TN * 32 + ch * (16 / ES);
+      if (gm < p.M && gn < p.N && DBG != 8 && DBG != 9) *(u32x4*)(C + gm * p.ldc + gn) = v;
     }
   }
 }
