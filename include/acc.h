@@ -51,8 +51,13 @@ enum {
 };
 
 enum {
-  ACC_FLAG_SKIP_SKETCH = 1u /* forward only: leave Xs untouched (several linears that share
-                               one input, e.g. q/k/v, keep a single Xs)                      */
+  ACC_FLAG_SKIP_SKETCH = 1u, /* forward only: leave Xs untouched (several linears that share
+                                one input, e.g. q/k/v, keep a single Xs)                     */
+  ACC_FLAG_ONE_LAUNCH = 2u   /* run the exact GEMM and the sketch of a pass as ONE kernel
+                                launch (their work-groups interleaved in one grid) when the
+                                shape allows it (bf16, r % 128 == 0, >= 192 output tiles of
+                                256 x 256); otherwise ignored.  Results are identical; on
+                                MI355X the default (two launches) is measured ~5 % faster. */
 };
 
 typedef struct acc_linear_desc {

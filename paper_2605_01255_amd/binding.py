@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libacc.so")
 
 ACC_F32, ACC_BF16 = 0, 1
 ACC_FLAG_SKIP_SKETCH = 1
+ACC_FLAG_ONE_LAUNCH = 2
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_philox_dump_u32",
            "acc_sketch_dump", "acc_status_string", "acc_version")

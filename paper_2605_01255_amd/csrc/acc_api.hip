@@ -9,6 +9,7 @@
 #include <utility>
 
 #include "acc_common.h"
+#include "acc_fused.h"
 #include "acc_gemm.h"
 #include "acc_generic.h"
 #include "acc_sketch.h"
@@ -28,7 +29,7 @@ struct Shape {
 
 int validate_desc(const acc_linear_desc* d, Shape* s) {
   if (!d) return ACC_ERR_INVALID_ARG;
-  if (d->flags & ~(uint32_t)ACC_FLAG_SKIP_SKETCH) return ACC_ERR_INVALID_ARG;
+  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
@@ -203,7 +204,8 @@ struct SketchPlan {
 
 SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, int64_t ld) {
   SketchPlan sp{};
-  sp.fast = d->io_dtype == ACC_BF16 && d->r % 64 == 0 && n * ld * 2 <= kMaxOperandBytes;
+  sp.fast = d->io_dtype == ACC_BF16 && d->r % 64 == 0 && n * ld * 2 <= kMaxOperandBytes &&
+            channels * d->r * 4 <= kMaxOperandBytes / 2;
   if (!sp.fast) {
     sp.G = generic_sketch_splits(n, channels, d->r);
     return sp;
@@ -221,6 +223,14 @@ SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, in
   if ((int64_t)sp.tokens_per_split * ld * 2 + 64 * ld * 2 > kMaxOperandBytes) sp.fast = false;
   if (!sp.fast) sp.G = generic_sketch_splits(n, channels, d->r);
   return sp;
+}
+
+void reduce_partials(const acc_linear_desc* d, const float* ws, int G, int64_t count, void* out, Launcher& L) {
+  const unsigned blocks = (unsigned)ceil_div(count, 1024);
+  if (d->factor_dtype == ACC_BF16)
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), ws, G, count, count, (bf16*)out);
+  else
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), ws, G, count, count, (float*)out);
 }
 
 // partial[g] (final orientation) with the tuned kernel, then K4 into `out`.
@@ -241,12 +251,38 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
     if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true, 0>, grid, dim3(256), lds, p);
     else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false, 0>, grid, dim3(256), lds, p);
   }
-  const int64_t count = channels * d->r;
-  const unsigned blocks = (unsigned)ceil_div(count, 1024);
-  if (d->factor_dtype == ACC_BF16)
-    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), (const float*)ws, sp.G, count, count, (bf16*)out);
-  else
-    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, sp.G, count, count, (float*)out);
+  reduce_partials(d, ws, sp.G, channels * d->r, out, L);
+}
+
+// One launch for the exact GEMM and the sketch of the same input (see acc_fused.h), then K4.
+// A [n, lda] is both the GEMM's left operand and the sketched matrix (X forward, dY backward).
+bool fused_ok(const acc_linear_desc* d, const SketchPlan& sp, int64_t n, int64_t N, int64_t K, int64_t lda,
+              int64_t ldb) {
+  return (d->flags & ACC_FLAG_ONE_LAUNCH) && d->io_dtype == ACC_BF16 && fast_gemm_ok(n, N, K, lda, ldb) &&
+         ceil_div(n, 256) * ceil_div(N, 256) >= 192 &&
+         sp.fast && sp.rc == 128;
+}
+
+template <bool KMAJ, bool TRANSPOSED>
+void fused_pass(const acc_linear_desc* d, const SketchPlan& sp, const void* A, const void* B, void* C, int64_t n,
+                int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, void* factor_out, float* ws,
+                Launcher& L) {
+  FastGemmParams gp{};
+  gp.A = (const bf16*)A; gp.B = (const bf16*)B; gp.C = C;
+  gp.M = n; gp.N = N; gp.K = K; gp.lda = lda; gp.ldb = ldb; gp.ldc = ldc;
+  const unsigned gemm_grid = gemm_bf16_plan(gp, 256, 256);
+  SketchFastParams sk{};
+  sk.A = (const bf16*)A; sk.part = ws; sk.n = n; sk.C = K; sk.lda = lda; sk.r = (int)d->r;
+  sk.tokens_per_split = sp.tokens_per_split; sk.n_cslab = sp.n_cslab; sk.n_js = sp.n_js; sk.G = sp.G;
+  sk.sk = make_sketch_params(d);
+  FuseMap fm{};
+  const int n_gg = (int)(gemm_grid / 8);
+  fm.unit = sp.n_js;
+  fm.n_units = (int)ceil_div((int64_t)sp.n_cslab * sp.G, 8);
+  fm.period = n_gg / fm.n_units;
+  const unsigned grid = (unsigned)(n_gg + fm.n_units * fm.unit) * 8u;
+  L.launch_lds(fused_linear_kernel<KMAJ, TRANSPOSED>, dim3(grid), dim3(512), (size_t)128 * 1024, gp, sk, fm);
+  reduce_partials(d, ws, sp.G, K * d->r, factor_out, L);
 }
 
 void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
@@ -289,6 +325,11 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
 
+  const SketchPlan sp_f = plan_sketch(desc, s.n, s.d_in, s.ldx);
+  if (sketch && fused_ok(desc, sp_f, s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
+    fused_pass<false, false>(desc, sp_f, X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, Xs, (float*)workspace, L);
+    return L.status();
+  }
   if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
     fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
   } else {
@@ -317,7 +358,12 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
 
-  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
+  const SketchPlan sp_b = plan_sketch(desc, s.n, s.d_out, s.ldy);
+  const bool fused_b = fused_ok(desc, sp_b, s.n, s.d_in, s.d_out, s.ldy, s.ldw);
+  if (fused_b) {
+    // W is [N = d_in, K = d_out]; the sketched matrix dY is the GEMM's left operand
+    fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, (float*)workspace, L);
+  } else if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
     fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);  // W is [N = d_in, K = d_out]
   } else {
     GemmParams p{};
@@ -328,7 +374,7 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
     generic_gemm_io(desc->io_dtype, p, L);
   }
   // Gr[j, c] = sum_i S[i, j] dY[i, c]: the contraction of dY^T with S, stored transposed.
-  run_sketch(desc, dY, s.ldy, s.d_out, s.n, true, Gr, (float*)workspace, L);
+  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, true, Gr, (float*)workspace, L);
   if (dW) {
     if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
       if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);

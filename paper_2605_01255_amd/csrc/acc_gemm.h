@@ -87,8 +87,7 @@ __device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)
 // Map the linear work-group id to an output tile so that the 32 tiles resident on one XCD
 // (work-groups are dealt round-robin to the 8 XCDs) form a super_m x super_n block that shares
 // A and B panels in that XCD's L2.  Returns false for padding work-groups.
-__device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int& tm, int& tn) {
-  const int b = blockIdx.x;
+__device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int b, int& tm, int& tn) {
   const int xcd = b & 7, local = b >> 3;
   const int sid = (local >> 5) * 8 + xcd;  // super-tile id, N fastest
   const int in = local & 31;
@@ -98,8 +97,9 @@ __device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int& tm, int& 
   return tm < p.tiles_m && tn < p.tiles_n;
 }
 
+// The work of one work-group: output tile number b (see xcd_tile), using the dynamic LDS at smem.
 template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0, int GS = 3>
-__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
+__device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, char* smem) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
   constexpr int A_BYTES = BM * BK * 2;
@@ -110,10 +110,9 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
   constexpr int BN_CHUNKS = BN / 8;             // 16-byte chunks per row of an N-contiguous B tile
   static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile/waves");
   static_assert(B_KMAJOR || (BN_CHUNKS >= 16 && 64 % BN_CHUNKS == 0), "B tile shape");
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   int tm, tn;
-  if (!xcd_tile(p, tm, tn)) return;
+  if (!xcd_tile(p, b, tm, tn)) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
@@ -331,6 +330,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p
       if (gm < p.M && gn < p.N && DBG != 8 && DBG != 9) *(u32x4*)(C + gm * p.ldc + gn) = v;
     }
   }
+}
+
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0, int GS = 3>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  gemm_bf16_tile<WM, WN, TM, TN, B_KMAJOR, TC, DBG, GS>(p, blockIdx.x, smem);
 }
 
 template <int WM, int WN, int TM, int TN>

@@ -31,6 +31,37 @@ struct SketchFastParams {
   SketchParams sk;
 };
 
+// Store one wave's fp32 partial tile (CWB blocks of 32 x 32) with buffer stores: the lane part of the
+// address is computed once, the (block, register) part is a scalar offset, and elements past the end
+// of the matrix fall outside the buffer resource and are dropped by the hardware.
+//   lane holds MFMA column (lane & 31) and rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4 of each block;
+//   !TRANSPOSED: rows = channels, columns = sketch columns, out[c * r + j]
+//    TRANSPOSED: rows = sketch columns, columns = channels, out[j * C + c]
+// cb0 = first channel of the wave's blocks, j0 = first sketch column of the wave.
+template <bool TRANSPOSED, int CWB>
+__device__ __forceinline__ void store_partial_tile(const f32x16 (&acc)[CWB], float* out, int64_t C, int r,
+                                                   int64_t cb0, int j0, int lane) {
+  const int lcol = lane & 31, kg = lane >> 5;
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc((void*)out, 0, (int)(uint32_t)(C * r * 4), 0x00020000);
+  uint32_t voff;
+  if (!TRANSPOSED) voff = (uint32_t)(((cb0 + kg * 4) * r + j0 + lcol) * 4);
+  else voff = (uint32_t)((((int64_t)(j0 + kg * 4)) * C + cb0 + lcol) * 4);
+#pragma unroll
+  for (int mb = 0; mb < CWB; ++mb) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int rowi = (e >> 2) * 8 + (e & 3);
+      const uint32_t soff = !TRANSPOSED ? (uint32_t)((mb * 32 + rowi) * r * 4)
+                                        : (uint32_t)((rowi * C + mb * 32) * 4);
+      const float v = acc[mb][e];
+      // transposed: a channel past the end would land in the next row, so it is sent out of range
+      const uint32_t vo = (TRANSPOSED && cb0 + mb * 32 + lcol >= C) ? 0xFFFFFFF0u : voff;
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, vo, soff, 0);
+    }
+  }
+}
+
 template <int WC, int WJ, int CWB, bool TRANSPOSED, int DBG = 0>
 __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastParams p) {
   constexpr int NW = WC * WJ;
@@ -167,8 +198,8 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
       } else {
         acc[mb][0] += (float)af[mb][0] * (float)sf[0];
       }
-      nf[mb] = read_block(rd_stage, mb);
-      sgen_slot(g, mb, gen_kstep, s_next);
+      if (DBG != 4) nf[mb] = read_block(rd_stage, mb);
+      if (DBG != 3) sgen_slot(g, mb, gen_kstep, s_next);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -182,8 +213,8 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   auto iteration = [&](int t, const bf16x8(&af)[CWB], bf16x8 sf, bf16x8(&nf)[CWB], SGen& g, bf16x8& s_next) {
     const int t_load = t + DEPTH < NS ? t + DEPTH : NS - 1;
     __builtin_amdgcn_sched_barrier(0);
-    issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
-    wait_oldest_stage();
+    if (DBG != 5) issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
+    if (DBG != 5) wait_oldest_stage();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     kstep_slots(af, sf, smem + ((t + 1) % NSTAGE) * STAGE, nf, g, t + 1, s_next);
@@ -199,6 +230,10 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
     __syncthreads();
 #pragma unroll
     for (int mb = 0; mb < CWB; ++mb) fa[mb] = read_block(smem, mb);
+    if (DBG == 4) {
+#pragma unroll
+      for (int mb = 0; mb < CWB; ++mb) fb[mb] = read_block(smem + STAGE, mb);
+    }
     int t = 0;
     for (; t + 1 < NS; t += 2) {
       iteration(t, fa, s_a, fb, gen, s_b);
@@ -209,25 +244,9 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   wait_vmcnt0();  // no transfer may still be in flight when the work-group's LDS is released
 
   // ---- store the fp32 partial tile ----
-  // lane holds MFMA column (lane & 31) and rows 8 * (e / 4) + 4 * (lane >> 5) + e % 4
-  float* __restrict__ out = p.part + (int64_t)g * p.C * p.r;
-  const int lcol = lane & 31, kg = lane >> 5;
-#pragma unroll
-  for (int mb = 0; mb < CWB; ++mb) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int rowi = (e >> 2) * 8 + kg * 4 + (e & 3);
-      if (!TRANSPOSED) {  // rows = channels, columns = sketch columns
-        const int64_t c = c0 + (wc * CWB + mb) * 32 + rowi;
-        const int64_t j = js * RC + wj * 32 + lcol;
-        if (c < p.C) out[c * p.r + j] = acc[mb][e];
-      } else {            // rows = sketch columns, columns = channels
-        const int64_t c = c0 + (wc * CWB + mb) * 32 + lcol;
-        const int64_t j = js * RC + wj * 32 + rowi;
-        if (c < p.C) out[j * p.C + c] = acc[mb][e];
-      }
-    }
-  }
+  if (DBG != 6)
+    store_partial_tile<TRANSPOSED, CWB>(acc, p.part + (int64_t)g * p.C * p.r, p.C, p.r, c0 + wc * CWB * 32,
+                                        js * RC + wj * 32, lane);
 }
 
 template <int WC, int WJ, int CWB>

@@ -48,7 +48,8 @@ def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, ro
     dW = torch.full((lin.d_in, lin.d_out), 7.0, dtype=acc.torch_dtype(dcode), device=device) if want_dw else None
     acc.acc_linear_fwd(desc, X, W, Y, Xs, acc.alloc_workspace(desc, False, device))
     bdesc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
-                          dw_dtype=dcode, row_offset=row_offset, ldx=desc.ldx, ldw=desc.ldw, ldy=desc.ldy)
+                          dw_dtype=dcode, row_offset=row_offset, ldx=desc.ldx, ldw=desc.ldw, ldy=desc.ldy,
+                          flags=flags & ~acc.ACC_FLAG_SKIP_SKETCH)
     acc.acc_linear_bwd(bdesc, dY, W, Xs, dX, Gr, dW, acc.alloc_workspace(bdesc, True, device))
     torch.cuda.synchronize()
     out = {"Y": acc.to_host_f64(Y), "Xs": acc.to_host_f64(Xs), "dX": acc.to_host_f64(dX),

@@ -152,3 +152,16 @@ def test_bf16_tuned_kernel_shapes(acc, n, d_in, d_out, r):
 def test_tuned_kernels_fp32_dw_and_strides(acc):
     lin = inputs.Linear("fast_strided", 1500, 512, 768, 128, dtype="bf16")
     _check(acc, lin, dw_dtype=0, pad=(64, 8, 72), row_offset=4 * 77, seed=0xABCDEF0123)
+
+
+def test_one_launch_flag_gives_identical_results(acc):
+    """ACC_FLAG_ONE_LAUNCH interleaves GEMM and sketch work-groups in one grid: same outputs, bit for bit
+    for the exact products, within tolerance of the oracle for the factors."""
+    lin = inputs.Linear("one_launch", 4100, 1024, 3080, 256, dtype="bf16")
+    data = inputs.make(lin)
+    two = gu.run_layer(acc, lin, data)
+    one = gu.run_layer(acc, lin, data, flags=acc.ACC_FLAG_ONE_LAUNCH)
+    assert np.array_equal(one["Y"], two["Y"]) and np.array_equal(one["dX"], two["dX"])
+    want = gu.run_oracle(lin, data)
+    for k in want:
+        assert gu.rel(one[k], want[k]) <= 1e-2, k
