@@ -24,13 +24,16 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c2", help="c1 | c2 | c3_r256 | c4 | c5 (a named linear: c4.k)")
     ap.add_argument("--no-dw", action="store_true", help="leave the dense dW out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--buffer-sets", type=int, default=3, help="rotated so no tensor stays in the 256 MB cache")
-    ap.add_argument("--all-linears", action="store_true", help="also print a per-linear table to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 5 times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--traffic-mb", type=float, default=None,
+                    help="HBM MB per launch of the dominant kernel, from rocprofv3 --pmc runs (goes into roofline.traffic)")
     return ap.parse_args()
 
 
@@ -119,6 +122,14 @@ def main():
         fwd(i)
         bwd(i)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -151,7 +162,9 @@ def main():
     achieved = gemm_flops / (ms_gemm * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "Y = X.W GEMM (acc_linear_fwd, sketch skipped)",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4), "traffic": None}
+                "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4),
+                "traffic": (args.traffic_mb * 1e6 if args.traffic_mb else None),
+                "algorithmic_bytes": (lin.n * lin.d_in + lin.d_in * lin.d_out + lin.n * lin.d_out) * 2}
 
     dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
     out = {
