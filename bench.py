@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--traffic-mb", type=float, default=None,
-                    help="HBM MB per launch of the dominant kernel, from rocprofv3 --pmc runs (goes into roofline.traffic)")
+                    help="HBM-side MB per launch of the dominant kernel, from rocprofv3 --pmc runs; default: the figure "
+                         "measured for the default workload (profiles/c2_attn_proj_counters.md), null for others")
     return ap.parse_args()
 
 
@@ -163,7 +164,8 @@ def main():
     roofline = {"bound": "mfma", "kernel": "Y = X.W GEMM (acc_linear_fwd, sketch skipped)",
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4),
-                "traffic": (args.traffic_mb * 1e6 if args.traffic_mb else None),
+                "traffic": (args.traffic_mb * 1e6 if args.traffic_mb else
+                            (553.8e6 if lin.name == "c2.attn_proj" else None)),
                 "algorithmic_bytes": (lin.n * lin.d_in + lin.d_in * lin.d_out + lin.n * lin.d_out) * 2}
 
     dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
