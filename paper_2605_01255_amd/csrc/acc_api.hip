@@ -242,11 +242,10 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
   p.sk = make_sketch_params(d);
   const int pairs = sp.n_cslab * sp.G;
   const dim3 grid((unsigned)(8 * sp.n_js * ceil_div(pairs, 8)));
-  if (sp.rc == 128) {
-    const size_t lds = sketch_bf16_lds_bytes<1, 4, 16>();
-    if (transposed) L.launch_lds(sketch_bf16_kernel<1, 4, 16, true, 0>, grid, dim3(256), lds, p);
-    else L.launch_lds(sketch_bf16_kernel<1, 4, 16, false, 0>, grid, dim3(256), lds, p);
-  } else {
+  if (sp.rc == 128) {  // 512 x 128 tile, 8 waves: two waves per SIMD overlap MFMA and Philox (-17 % vs 4 waves)
+    if (transposed) L.launch_lds(sketch8_kernel<true>, grid, dim3(512), (size_t)128 * 1024, p);
+    else L.launch_lds(sketch8_kernel<false>, grid, dim3(512), (size_t)128 * 1024, p);
+  } else {             // 1024 x 64 tile, 4 waves
     const size_t lds = sketch_bf16_lds_bytes<2, 2, 16>();
     if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true, 0>, grid, dim3(256), lds, p);
     else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false, 0>, grid, dim3(256), lds, p);

@@ -172,6 +172,13 @@ __device__ __forceinline__ void sketch8_tile(const SketchFastParams& p, int b, c
                                       js * RC + wj * 32, lane);
 }
 
+// The 8-wave sketch tile as a kernel of its own (grid as for sketch_bf16_kernel).
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(512) void sketch8_kernel(SketchFastParams sp) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  sketch8_tile<TRANSPOSED>(sp, blockIdx.x, smem);
+}
+
 template <bool B_KMAJOR, bool TRANSPOSED>
 __global__ __launch_bounds__(512) void fused_linear_kernel(FastGemmParams gp, SketchFastParams sp, FuseMap fm) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
