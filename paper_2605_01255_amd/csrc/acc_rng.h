@@ -31,6 +31,14 @@ __device__ __forceinline__ float uniform_from_word(uint32_t x) {
   return ((float)(x >> 9) + 0.5f) * 0x1p-23f;  // every step exact in fp32
 }
 
+// a ^ b ^ k in one instruction (v_bitop3_b32 with truth table 0x96 = three-input xor; k wave-uniform).
+// The compiler emits two v_xor_b32 here.
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t k) {
+  uint32_t r;
+  asm("v_bitop3_b32 %0, %1, %2, %3 bitop3:0x96" : "=v"(r) : "v"(a), "v"(b), "s"(k));
+  return r;
+}
+
 // One Philox4x32 round on a counter held in c[0..3]; round_index selects the bumped key (wave-uniform).
 __device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t key0, uint32_t key1, int round_index) {
   const uint32_t k0 = key0 + (uint32_t)round_index * 0x9E3779B9u;
@@ -39,7 +47,7 @@ __device__ __forceinline__ void philox_round(uint32_t (&c)[4], uint32_t key0, ui
   const uint64_t p1 = (uint64_t)0xCD9E8D57u * c[2];
   const uint32_t hi0 = (uint32_t)(p0 >> 32), lo0 = (uint32_t)p0;
   const uint32_t hi1 = (uint32_t)(p1 >> 32), lo1 = (uint32_t)p1;
-  const uint32_t n0 = hi1 ^ c[1] ^ k0, n2 = hi0 ^ c[3] ^ k1;
+  const uint32_t n0 = xor3(hi1, c[1], k0), n2 = xor3(hi0, c[3], k1);
   c[0] = n0; c[1] = lo1; c[2] = n2; c[3] = lo0;
 }
 
