@@ -186,7 +186,8 @@ def main():
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
-        budget = 2048 if lin.n * lin.d_in * lin.d_out > 1e10 else lin.n
+        # the whole 3B-shaped projection is ~1-2 s of fp64 BLAS on the machine's cores; larger shapes are sampled
+        budget = lin.n if lin.flops(with_dw) <= 1.5e12 else max(1024, int(lin.n * 1.5e12 / lin.flops(with_dw)) // 256 * 256)
         out["cpu_baseline"] = cpu_baseline(lin, data, with_dw, budget)
     print(json.dumps(out), flush=True)
 

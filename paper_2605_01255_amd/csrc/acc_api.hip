@@ -185,11 +185,11 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
   const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
   if (big_tiles >= 192) {  // 256 x 256 tiles, 8 waves: enough tiles to fill 256 CUs
     const unsigned grid = gemm_bf16_plan(p, 256, 256);
-    L.launch_lds(gemm_bf16_kernel<2, 4, 4, 2, KMAJ, TC, 0>, dim3(grid), dim3(512),
+    L.launch_lds(gemm_bf16_kernel<2, 4, 4, 2, KMAJ, TC>, dim3(grid), dim3(512),
                  (size_t)gemm_bf16_lds_bytes<2, 4, 4, 2>(), p);
   } else {                 // 128 x 128 tiles, 4 waves
     const unsigned grid = gemm_bf16_plan(p, 128, 128);
-    L.launch_lds(gemm_bf16_kernel<2, 2, 2, 2, KMAJ, TC, 0>, dim3(grid), dim3(256),
+    L.launch_lds(gemm_bf16_kernel<2, 2, 2, 2, KMAJ, TC>, dim3(grid), dim3(256),
                  (size_t)gemm_bf16_lds_bytes<2, 2, 2, 2>(), p);
   }
 }
@@ -247,8 +247,8 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
     else L.launch_lds(sketch8_kernel<false>, grid, dim3(512), (size_t)128 * 1024, p);
   } else {             // 1024 x 64 tile, 4 waves
     const size_t lds = sketch_bf16_lds_bytes<2, 2, 16>();
-    if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true, 0>, grid, dim3(256), lds, p);
-    else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false, 0>, grid, dim3(256), lds, p);
+    if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true>, grid, dim3(256), lds, p);
+    else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false>, grid, dim3(256), lds, p);
   }
   reduce_partials(d, ws, sp.G, channels * d->r, out, L);
 }

@@ -98,7 +98,7 @@ __device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int b, int& tm
 }
 
 // The work of one work-group: output tile number b (see xcd_tile), using the dynamic LDS at smem.
-template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0, int GS = 3>
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC>
 __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, char* smem) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
@@ -123,7 +123,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   // supplies the chunk that belongs at position i of that kilobyte.  Sources are byte offsets into
   // buffer resources that start at the tile's first row / column; rows past the end of the matrix
   // read as zero (their products are never stored).
-  const int64_t am0 = DBG == 7 ? 0 : m0, bn0 = DBG == 7 ? 0 : n0;
+  const int64_t am0 = m0, bn0 = n0;
   const u32x4 a_rsrc = make_rsrc(p.A + am0 * p.lda, ((p.M - am0 - 1) * p.lda + p.K) * 2);
   const u32x4 b_rsrc =
       B_KMAJOR ? make_rsrc(p.B + bn0 * p.ldb, ((p.N - bn0 - 1) * p.ldb + p.K) * 2)
@@ -192,16 +192,6 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  auto mfma_step = [&](const bf16x8(&af)[TM], const bf16x8(&bfr)[TN]) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        else acc[i][j][0] += (float)af[i][0] * (float)bfr[j][0];
-      }
-  };
-
   const int KT = (int)(p.K / BK);
   bf16x8 af[2][TM], bfr[2][TN];
 
@@ -229,7 +219,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   // while the texture path drains and starves the MFMA pipe.
   constexpr int NM = TM * TN;
   constexpr int NG_TOTAL = A_LOADS + B_LOADS;
-  constexpr int G_STEPS = GS;                                  // k-steps that carry wave-loads
+  constexpr int G_STEPS = 3;                                   // k-steps that carry wave-loads
   constexpr int G_PER_STEP = (NG_TOTAL + G_STEPS - 1) / G_STEPS;
   constexpr int G_EVERY = NM / G_PER_STEP > 0 ? NM / G_PER_STEP : 1;
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s,
@@ -239,16 +229,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       const int i = q / TN, j = q % TN;
       // B operand first: the product comes out transposed, lane = output row, 4 consecutive registers =
       // 4 consecutive output columns, which is what the epilogue packs
-      if (DBG != 2) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
-      else acc[i][j][0] += (float)ca[i][0] * (float)cb[j][0];
-      if (DBG != 5 && DBG != 9) {
-        if (q < TM) read_a1(rd_stage, rd_s, q, na);
-        else if (q < TM + TN) read_b1(rd_stage, rd_s, q - TM, nb);
-      }
-      if (DBG != 1 && DBG != 5 && DBG != 6 && DBG != 9) {
-        if (q % G_EVERY == 0 && q / G_EVERY < g_count && g_first + q / G_EVERY < NG_TOTAL)
-          issue_one(g_first + q / G_EVERY, kt_next, nxt);
-      }
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
+      if (q < TM) read_a1(rd_stage, rd_s, q, na);
+      else if (q < TM + TN) read_b1(rd_stage, rd_s, q - TM, nb);
+      if (q % G_EVERY == 0 && q / G_EVERY < g_count && g_first + q / G_EVERY < NG_TOTAL)
+        issue_one(g_first + q / G_EVERY, kt_next, nxt);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -262,12 +247,6 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   for (int i = 0; i < TM; ++i) read_a1(smem, 0, i, af[0]);
 #pragma unroll
   for (int j = 0; j < TN; ++j) read_b1(smem, 0, j, bfr[0]);
-  if (DBG == 5) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i) read_a1(smem, 1, i, af[1]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) read_b1(smem, 1, j, bfr[1]);
-  }
 
   for (int kt = 0; kt < KT; ++kt) {
     const char* cur = smem + (kt & 1) * STAGE;
@@ -277,12 +256,12 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
     const int kt_next = kt + 1 < KT ? kt + 1 : kt;
     __builtin_amdgcn_sched_barrier(0);
     kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_STEPS > 1 ? G_PER_STEP : 0, kt_next, nxt_lds);
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_STEPS > 2 ? G_PER_STEP : 0, kt_next, nxt_lds);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
     // The next tile must have landed (every wave's transfers) before anyone reads it, and every
     // wave must be done reading `cur` before the tile after next is written over it.
     wait_vmcnt0();
-    if (DBG != 6) __syncthreads();
+    __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     // last k-step of this tile covers the latency of the first operand reads of the next one
     kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt_lds);
@@ -327,15 +306,15 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       const u32x4 v = *(const u32x4*)(stage_w + row * PITCH + ch * 16);
       const int64_t gm = m0 + (wm * TM + i) * 32 + row;
       const int64_t gn = n0 + wn * TN * 32 + ch * (16 / ES);
-      if (gm < p.M && gn < p.N && DBG != 8 && DBG != 9) *(u32x4*)(C + gm * p.ldc + gn) = v;
+      if (gm < p.M && gn < p.N) *(u32x4*)(C + gm * p.ldc + gn) = v;
     }
   }
 }
 
-template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, int DBG = 0, int GS = 3>
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  gemm_bf16_tile<WM, WN, TM, TN, B_KMAJOR, TC, DBG, GS>(p, blockIdx.x, smem);
+  gemm_bf16_tile<WM, WN, TM, TN, B_KMAJOR, TC>(p, blockIdx.x, smem);
 }
 
 template <int WM, int WN, int TM, int TN>

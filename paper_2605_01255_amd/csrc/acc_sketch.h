@@ -62,7 +62,7 @@ __device__ __forceinline__ void store_partial_tile(const f32x16 (&acc)[CWB], flo
   }
 }
 
-template <int WC, int WJ, int CWB, bool TRANSPOSED, int DBG = 0>
+template <int WC, int WJ, int CWB, bool TRANSPOSED>
 __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastParams p) {
   constexpr int NW = WC * WJ;
   constexpr int CH = WC * CWB * 32, RC = WJ * 32, BT = 16;
@@ -192,14 +192,10 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
                          int gen_kstep, bf16x8& s_next) {
 #pragma unroll
     for (int mb = 0; mb < CWB; ++mb) {
-      if (DBG != 2) {
-        if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, af[mb], acc[mb], 0, 0, 0);
-        else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], sf, acc[mb], 0, 0, 0);
-      } else {
-        acc[mb][0] += (float)af[mb][0] * (float)sf[0];
-      }
-      if (DBG != 4) nf[mb] = read_block(rd_stage, mb);
-      if (DBG != 3) sgen_slot(g, mb, gen_kstep, s_next);
+      if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, af[mb], acc[mb], 0, 0, 0);
+      else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], sf, acc[mb], 0, 0, 0);
+      nf[mb] = read_block(rd_stage, mb);
+      sgen_slot(g, mb, gen_kstep, s_next);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -213,8 +209,8 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   auto iteration = [&](int t, const bf16x8(&af)[CWB], bf16x8 sf, bf16x8(&nf)[CWB], SGen& g, bf16x8& s_next) {
     const int t_load = t + DEPTH < NS ? t + DEPTH : NS - 1;
     __builtin_amdgcn_sched_barrier(0);
-    if (DBG != 5) issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
-    if (DBG != 5) wait_oldest_stage();
+    issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
+    wait_oldest_stage();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     kstep_slots(af, sf, smem + ((t + 1) % NSTAGE) * STAGE, nf, g, t + 1, s_next);
@@ -230,10 +226,6 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
     __syncthreads();
 #pragma unroll
     for (int mb = 0; mb < CWB; ++mb) fa[mb] = read_block(smem, mb);
-    if (DBG == 4) {
-#pragma unroll
-      for (int mb = 0; mb < CWB; ++mb) fb[mb] = read_block(smem + STAGE, mb);
-    }
     int t = 0;
     for (; t + 1 < NS; t += 2) {
       iteration(t, fa, s_a, fb, gen, s_b);
@@ -244,9 +236,8 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   wait_vmcnt0();  // no transfer may still be in flight when the work-group's LDS is released
 
   // ---- store the fp32 partial tile ----
-  if (DBG != 6)
-    store_partial_tile<TRANSPOSED, CWB>(acc, p.part + (int64_t)g * p.C * p.r, p.C, p.r, c0 + wc * CWB * 32,
-                                        js * RC + wj * 32, lane);
+  store_partial_tile<TRANSPOSED, CWB>(acc, p.part + (int64_t)g * p.C * p.r, p.C, p.r, c0 + wc * CWB * 32,
+                                      js * RC + wj * 32, lane);
 }
 
 template <int WC, int WJ, int CWB>
