@@ -70,6 +70,25 @@ int check_device() {
   return cached[dev] == 1 ? ACC_OK : ACC_ERR_HIP;
 }
 
+// Kernels whose dynamic-LDS limit has been raised on a device (the attribute sticks to the function, so
+// it is set once per kernel and device, not per launch).  A benign race only sets it twice.
+struct RaisedEntry { const void* kernel; int device; };
+RaisedEntry g_raised[64];
+int g_raised_count = 0;
+bool lds_limit_raised(const void* kernel) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  for (int i = 0; i < g_raised_count && i < 64; ++i)
+    if (g_raised[i].kernel == kernel && g_raised[i].device == dev) return true;
+  return false;
+}
+void lds_limit_note(const void* kernel) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return;
+  const int i = g_raised_count;
+  if (i < 64) { g_raised[i] = RaisedEntry{kernel, dev}; g_raised_count = i + 1; }
+}
+
 // Enqueues kernels on one stream and remembers the first launch error.
 struct Launcher {
   hipStream_t st;
@@ -83,8 +102,11 @@ struct Launcher {
   void launch_lds(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, Args... args) {
     if (err != hipSuccess) return;
     if (lds_bytes > 64 * 1024) {
-      err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-      if (err != hipSuccess) return;
+      if (!lds_limit_raised((const void*)kernel)) {
+        err = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (err != hipSuccess) return;
+        lds_limit_note((const void*)kernel);
+      }
     }
     std::tuple<KArgs...> vals{args...};
     void* ptrs[sizeof...(KArgs)];
