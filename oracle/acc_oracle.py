@@ -7,6 +7,8 @@ What it computes (spec notation; the paper's is in brackets):
   backward  dX = dY . W^T             exact input gradient    [Def. 3.1: G_X = (grad_Z L) W; Thm 3.2.2(a)]
             Gr = S^T . dY             small gradient factor   [Sec. 4: ((grad_Z L)^T U)^T]
             dW = Xs . Gr              factored weight grad    [Sec. 4: G^_W = ((grad_Z L)^T U) V^T, transposed]
+            dB = 1^T . dY             bias gradient, exact    [proof of Thm 3.2.2, bias term]
+  With w_out_in=True W, Gr and dW are in the paper's own orientation ([d_out, d_in], [d_out, r]).
 
 S is the n x r random-projection compressor (the paper's "RP" option, Experimental
 Setup) taken along the token axis with i.i.d. N(0, 1/r) entries, so that
@@ -32,7 +34,8 @@ identities and normal moments / KS distance; integer matrices against pure-Pytho
 loops; exactness with an orthogonal S at r = n; Monte-Carlo unbiasedness
 (Thm 3.2.1(a)); the Gaussian-sketch variance closed form (Thm 3.3.1 per-layer
 term); the 1/sqrt(r) error law matching the paper's RP error table; dX independent
-of seed and rank (Thm 3.2.2(a)).  No function here is "parity unpinned".
+of seed and rank (Thm 3.2.2(a)); the bias gradient against a finite difference of the
+affine layer's loss; the [d_out, d_in] orientation against index loops in the paper's form.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -111,29 +114,50 @@ def sketch_matrix(seed: int, n: int, r: int, row_offset: int = 0):
     return z / np.sqrt(float(r))
 
 
-def linear_fwd(X, W, seed: int = 0, r: int = 0, row_offset: int = 0, S=None):
-    """Y = X W (exact), Xs = X^T S (the stored factor)."""
+def linear_fwd(X, W, seed: int = 0, r: int = 0, row_offset: int = 0, S=None, w_out_in: bool = False):
+    """Y = X W (exact), Xs = X^T S (the stored factor).
+
+    w_out_in: W is given as [d_out, d_in], the paper's own orientation (Def. 3.1: Z = X W^T).
+    """
     X = np.asarray(X, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
     if S is None:
         S = sketch_matrix(seed, X.shape[0], r, row_offset)
-    Y = np.matmul(X, W)
+    Y = np.matmul(X, W.T) if w_out_in else np.matmul(X, W)
     Xs = np.matmul(X.T, S)
     return Y, Xs
 
 
 def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None,
-               want_dW: bool = True):
-    """dX = dY W^T (exact), Gr = S^T dY, dW = Xs Gr (optional)."""
+               want_dW: bool = True, w_out_in: bool = False):
+    """dX = dY W^T (exact), Gr = S^T dY, dW = Xs Gr (optional).
+
+    w_out_in: W is [d_out, d_in] and the gradient side follows the paper's orientation (Sec. 4):
+    the factor is (grad_Z L)^T U = dY^T S, [d_out, r], and the weight gradient is
+    G^_W = (dY^T S) (X^T S)^T, [d_out, d_in] like W.
+    """
     dY = np.asarray(dY, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
     Xs = np.asarray(Xs, dtype=np.float64)
     if S is None:
         S = sketch_matrix(seed, dY.shape[0], r, row_offset)
-    dX = np.matmul(dY, W.T)
-    Gr = np.matmul(S.T, dY)
-    dW = np.matmul(Xs, Gr) if want_dW else None
+    if w_out_in:
+        dX = np.matmul(dY, W)
+        Gr = np.matmul(dY.T, S)
+        dW = np.matmul(Gr, Xs.T) if want_dW else None
+    else:
+        dX = np.matmul(dY, W.T)
+        Gr = np.matmul(S.T, dY)
+        dW = np.matmul(Xs, Gr) if want_dW else None
     return dX, Gr, dW
+
+
+def bias_grad(dY):
+    """Gradient of a bias b [d_out] broadcast over tokens, Z = X W^T + 1 b^T (proof of Thm 3.2.2,
+    bias term): the loss gradient w.r.t. the added term is grad_Z L itself, independent of X and
+    therefore exact under compression; summed over the tokens that share b it is the column sum of dY.
+    """
+    return np.sum(np.asarray(dY, dtype=np.float64), axis=0)
 
 
 def reconstruct_activation(Xs, seed: int, n: int, r: int, row_offset: int = 0, S=None):

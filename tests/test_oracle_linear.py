@@ -119,3 +119,58 @@ def test_bf16_rounding_helper():
     assert got[2] == 1.0 + 2.0 ** -6           # tie -> even mantissa (rounds up)
     assert got[3] == -2.5
     assert np.all(np.abs(got[:4] - vals[:4]) <= 2.0 ** -8 * np.abs(vals[:4]))
+
+
+def test_paper_orientation_against_index_loops():
+    """w_out_in: W [d_out, d_in] as in Def. 3.1 (Z = X W^T); factor and weight gradient as in Sec. 4.
+
+    Written as index sums straight from the definitions, with Python integers.
+    """
+    rng = np.random.default_rng(3)
+    n, d_in, d_out, r = 6, 4, 5, 3
+    X, W, dY, S = _ints(rng, (n, d_in)), _ints(rng, (d_out, d_in)), _ints(rng, (n, d_out)), _ints(rng, (n, r))
+    Sf = S.astype(np.float64)
+    Y, Xs = orc.linear_fwd(X, W, S=Sf, w_out_in=True)
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=Sf, w_out_in=True)
+    assert Y.shape == (n, d_out) and dX.shape == (n, d_in) and Gr.shape == (d_out, r) and dW.shape == (d_out, d_in)
+    for i in range(n):
+        for o in range(d_out):
+            assert Y[i, o] == sum(int(X[i, c]) * int(W[o, c]) for c in range(d_in))
+        for c in range(d_in):
+            assert dX[i, c] == sum(int(dY[i, o]) * int(W[o, c]) for o in range(d_out))
+    for o in range(d_out):
+        for j in range(r):
+            assert Gr[o, j] == sum(int(dY[i, o]) * int(S[i, j]) for i in range(n))
+        for c in range(d_in):
+            want = sum(sum(int(dY[i, o]) * int(S[i, j]) for i in range(n)) *
+                       sum(int(X[i, c]) * int(S[i, j]) for i in range(n)) for j in range(r))
+            assert dW[o, c] == want
+    # the two orientations describe the same layer
+    Y2, Xs2 = orc.linear_fwd(X, W.T, S=Sf)
+    dX2, Gr2, dW2 = orc.linear_bwd(dY, W.T, Xs2, S=Sf)
+    assert np.array_equal(Y, Y2) and np.array_equal(Xs, Xs2) and np.array_equal(dX, dX2)
+    assert np.array_equal(Gr, Gr2.T) and np.array_equal(dW, dW2.T)
+
+
+def test_bias_gradient_is_the_derivative_of_the_affine_layer():
+    """Proof of Thm 3.2.2 (bias term): for Z = X W + 1 b^T and a loss whose gradient w.r.t. Z is dY,
+    dL/db is the column sum of dY, whatever X is.  Checked against a central finite difference of the
+    linear loss L(b) = <dY, X W + 1 b^T> (exact for a linear function up to rounding) and against
+    integer loops."""
+    rng = np.random.default_rng(4)
+    n, d_in, d_out = 9, 4, 6
+    X, W = rng.standard_normal((n, d_in)), rng.standard_normal((d_in, d_out))
+    dY = rng.standard_normal((n, d_out))
+    b = rng.standard_normal(d_out)
+    dB = orc.bias_grad(dY)
+    assert dB.shape == (d_out,)
+    loss = lambda bb: float(np.sum(dY * (X @ W + bb[None, :])))
+    h = 0.5
+    for o in range(d_out):
+        e = np.zeros(d_out); e[o] = h
+        fd = (loss(b + e) - loss(b - e)) / (2 * h)
+        assert abs(fd - dB[o]) < 1e-9 * (1 + abs(dB[o]))
+    # independent of the activation: a different X gives the same gradient (it never enters)
+    Di = _ints(rng, (5, 3))
+    assert orc.bias_grad(Di).tolist() == [sum(int(Di[i, o]) for i in range(5)) for o in range(3)]
+    assert orc.bias_grad(np.zeros((0, 4))).tolist() == [0.0] * 4
