@@ -185,6 +185,35 @@ def main():
                                        "ratio": round(dense_b / kept_b, 2)},
         "roofline": roofline,
     }
+    # rows added after the hot path: bias gradient (HBM-bound column sum of dY) and the layer with W in
+    # the [d_out, d_in] orientation; reported beside the headline, not part of `value`
+    tdt = acc.torch_dtype(code)
+    dB = torch.empty(lin.d_out, dtype=tdt, device=dev)
+
+    def bias_grad(i):
+        acc.acc_linear_bias_grad(desc, sets[i % len(sets)].dY, dB, ws_b)
+
+    bias_grad(0)
+    ms_db = time_events(torch, bias_grad, args.steps)
+    db_bytes = lin.n * lin.d_out * (2 if lin.dtype == "bf16" else 4)
+    desc_oi = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code,
+                            flags=acc.ACC_FLAG_W_OUT_IN)
+    w_oi = [b.W.t().contiguous() for b in sets]
+    gr_oi = torch.empty(lin.d_out, lin.r, dtype=tdt, device=dev)
+    dw_oi = torch.empty(lin.d_out, lin.d_in, dtype=tdt, device=dev) if with_dw else None
+
+    def step_oi(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd(desc_oi, b.X, w_oi[i % len(sets)], b.Y, b.Xs, ws_f)
+        acc.acc_linear_bwd(desc_oi, b.dY, w_oi[i % len(sets)], b.Xs, b.dX, gr_oi, dw_oi, ws_b)
+
+    step_oi(0)
+    ms_oi = time_events(torch, step_oi, args.steps)
+    out["widened"] = {
+        "bias_grad": {"ms": round(ms_db, 4), "bound": "hbm", "achieved": round(db_bytes / (ms_db * 1e-3) / 1e9, 1),
+                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(db_bytes / (ms_db * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+        "w_out_in": {"ms_per_step": round(ms_oi, 4), "value": round(flops / (ms_oi * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},
+    }
     if not args.no_cpu_baseline:
         # the whole 3B-shaped projection is ~1-2 s of fp64 BLAS on the machine's cores; larger shapes are sampled
         budget = lin.n if lin.flops(with_dw) <= 1.5e12 else max(1024, int(lin.n * 1.5e12 / lin.flops(with_dw)) // 256 * 256)

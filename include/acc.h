@@ -11,6 +11,11 @@
  *   dX [n, d_in]      dX = dY.W^T  exact input gradient
  *   Gr [r, d_out]     Gr = S^T.dY  small factor of the weight gradient
  *   dW [d_in, d_out]  dW = Xs.Gr   factored weight gradient, materialised on request
+ *   dB [d_out]        dB = 1^T.dY  gradient of a bias broadcast over tokens (exact)
+ *
+ * With ACC_FLAG_W_OUT_IN the weight side is in the paper's own orientation (Def. 3.1: Z = X.W^T;
+ * Sec. 4): W [d_out, d_in], Gr [d_out, r] = dY^T.S, dW [d_out, d_in] = Gr.Xs^T.  X, Y, dY, dX and
+ * Xs are unchanged, and every result equals the transpose of its default-orientation counterpart.
  *
  * Random stream: Philox4x32-10 with key (seed low word, seed high word) and counter
  * ((g >> 2) low word, j, 0, g >> 34), g = row_offset + i; output word w of the call is
@@ -52,12 +57,15 @@ enum {
 
 enum {
   ACC_FLAG_SKIP_SKETCH = 1u, /* forward only: leave Xs untouched (several linears that share
-                                one input, e.g. q/k/v, keep a single Xs)                     */
-  ACC_FLAG_ONE_LAUNCH = 2u   /* run the exact GEMM and the sketch of a pass as ONE kernel
+                                one input, e.g. q/k/v, keep a single Xs; Sec. 5.1)           */
+  ACC_FLAG_ONE_LAUNCH = 2u,  /* run the exact GEMM and the sketch of a pass as ONE kernel
                                 launch (their work-groups interleaved in one grid) when the
                                 shape allows it (bf16, r % 128 == 0, >= 192 output tiles of
                                 256 x 256); otherwise ignored.  Results are identical; on
                                 MI355X the default (two launches) is measured ~5 % faster. */
+  ACC_FLAG_W_OUT_IN = 4u     /* W is [d_out, ldw >= d_in] (the layout of torch.nn.Linear.weight
+                                and of the paper's Def. 3.1); Gr is then [d_out, r] and dW
+                                [d_out, d_in].  ACC_FLAG_ONE_LAUNCH is ignored with it.          */
 };
 
 typedef struct acc_linear_desc {
@@ -66,7 +74,7 @@ typedef struct acc_linear_desc {
   int64_t d_out;        /* output features, multiple of 8                                    */
   int64_t r;            /* sketch rank, multiple of 16                                       */
   int64_t ldx;          /* row stride of X and dX in elements; 0 = d_in                      */
-  int64_t ldw;          /* row stride of W in elements;        0 = d_out                     */
+  int64_t ldw;          /* row stride of W in elements;        0 = d_out (d_in with W_OUT_IN) */
   int64_t ldy;          /* row stride of Y and dY in elements; 0 = d_out                     */
   uint64_t seed;        /* Philox key                                                        */
   uint64_t row_offset;  /* global index of local token 0 (multiple of 4); 0 on one GPU      */
@@ -95,6 +103,16 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
  * are read.  Xs may be NULL when dW is NULL. */
 int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, const void* Xs,
                    void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream);
+
+/* Gradient of a bias b [d_out] that is broadcast over tokens (proof of Thm 3.2.2, bias term: the
+ * gradient of the added term is grad_Z L itself, independent of X, hence exact under compression):
+ * dB[o] = sum_i dY[i, o], accumulated in fp32 in a fixed order (bitwise reproducible), stored as
+ * desc->dw_dtype.  dY [n, ldy] (io_dtype) is read; dB [d_out] is overwritten.  Needs the backward
+ * workspace: ws_bytes >= acc_linear_workspace_bytes(desc, 1); contents are scratch, so on one stream it
+ * may be the buffer acc_linear_bwd uses.  Only n, d_out, r, ldy, io_dtype, factor_dtype, dw_dtype of
+ * desc matter (r and factor_dtype through the workspace size only). */
+int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, void* workspace,
+                         size_t ws_bytes, void* stream);
 
 /* Test hook: the Philox integer stream behind S.  out is a device array of
  * ceil(n/4) * r * 4 uint32 laid out [token group q][column j][word w]. */

@@ -15,8 +15,10 @@ LIB_PATH = os.path.join(_HERE, "libacc.so")
 ACC_F32, ACC_BF16 = 0, 1
 ACC_FLAG_SKIP_SKETCH = 1
 ACC_FLAG_ONE_LAUNCH = 2
+ACC_FLAG_W_OUT_IN = 4
 
-EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_philox_dump_u32",
+EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
+           "acc_philox_dump_u32",
            "acc_sketch_dump", "acc_status_string", "acc_version")
 
 
@@ -51,6 +53,8 @@ _lib.acc_linear_fwd.restype = ctypes.c_int
 _lib.acc_linear_fwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_linear_bwd.restype = ctypes.c_int
 _lib.acc_linear_bwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_bias_grad.restype = ctypes.c_int
+_lib.acc_linear_bias_grad.argtypes = [_dp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_philox_dump_u32.restype = ctypes.c_int
 _lib.acc_philox_dump_u32.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64, _vp, _vp]
 _lib.acc_sketch_dump.restype = ctypes.c_int
@@ -120,6 +124,14 @@ def acc_linear_bwd(desc, dY, W, Xs, dX, Gr, dW, workspace, stream=None, ws_bytes
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.acc_linear_bwd(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(Xs), _ptr(dX), _ptr(Gr),
                                _ptr(dW), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_bias_grad(desc, dY, dB, workspace, stream=None, ws_bytes=None):
+    """Enqueue dB = column sums of dY (workspace: the backward one)."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_linear_bias_grad(ctypes.byref(desc), _ptr(dY), _ptr(dB), _ptr(workspace), ws_bytes,
+                                     _stream(stream)))
 
 
 def acc_philox_dump_u32(seed, row_offset, n, r, out, stream=None):

@@ -29,7 +29,7 @@ struct Shape {
 
 int validate_desc(const acc_linear_desc* d, Shape* s) {
   if (!d) return ACC_ERR_INVALID_ARG;
-  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
+  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN)) return ACC_ERR_INVALID_ARG;
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
@@ -39,9 +39,10 @@ int validate_desc(const acc_linear_desc* d, Shape* s) {
   if (d->row_offset % 4) return ACC_ERR_SHAPE;
   s->n = d->n; s->d_in = d->d_in; s->d_out = d->d_out; s->r = d->r;
   s->ldx = d->ldx ? d->ldx : d->d_in;
-  s->ldw = d->ldw ? d->ldw : d->d_out;
+  const int64_t w_row = (d->flags & ACC_FLAG_W_OUT_IN) ? d->d_in : d->d_out;  // elements per row of W
+  s->ldw = d->ldw ? d->ldw : w_row;
   s->ldy = d->ldy ? d->ldy : d->d_out;
-  if (s->ldx < s->d_in || s->ldw < s->d_out || s->ldy < s->d_out) return ACC_ERR_SHAPE;
+  if (s->ldx < s->d_in || s->ldw < w_row || s->ldy < s->d_out) return ACC_ERR_SHAPE;
   if (s->ldx % 8 || s->ldw % 8 || s->ldy % 8) return ACC_ERR_SHAPE;
   return ACC_OK;
 }
@@ -178,9 +179,15 @@ void generic_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_
 
 void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const void* Gr, void* dW, Launcher& L) {
   GemmParams p{};
-  p.A = Xs; p.B = Gr; p.C = dW;
-  p.M = s.d_in; p.N = s.d_out; p.K = s.r;
-  p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
+  if (d->flags & ACC_FLAG_W_OUT_IN) {  // dW [d_out, d_in] = Gr [d_out, r] . Xs^T
+    p.A = Gr; p.B = Xs; p.C = dW;
+    p.M = s.d_out; p.N = s.d_in; p.K = s.r;
+    p.a_sm = s.r; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.r; p.c_sm = s.d_in; p.c_sn = 1;
+  } else {
+    p.A = Xs; p.B = Gr; p.C = dW;
+    p.M = s.d_in; p.N = s.d_out; p.K = s.r;
+    p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
+  }
   p.k_per_split = round_up(s.r, 32);
   const bool fb = d->factor_dtype == ACC_BF16, ob = d->dw_dtype == ACC_BF16;
   if (fb && ob) launch_generic<bf16, bf16, bf16, bf16, false, false>(p, 1, L);
@@ -279,7 +286,7 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
 // A [n, lda] is both the GEMM's left operand and the sketched matrix (X forward, dY backward).
 bool fused_ok(const acc_linear_desc* d, const SketchPlan& sp, int64_t n, int64_t N, int64_t K, int64_t lda,
               int64_t ldb) {
-  return (d->flags & ACC_FLAG_ONE_LAUNCH) && d->io_dtype == ACC_BF16 && fast_gemm_ok(n, N, K, lda, ldb) &&
+  return (d->flags & ACC_FLAG_ONE_LAUNCH) && !(d->flags & ACC_FLAG_W_OUT_IN) && d->io_dtype == ACC_BF16 && fast_gemm_ok(n, N, K, lda, ldb) &&
          ceil_div(n, 256) * ceil_div(N, 256) >= 192 &&
          sp.fast && sp.rc == 128;
 }
@@ -354,13 +361,16 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
   // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
   // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
   if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L);
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W is [N = d_out, K = d_in]
   if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
-    fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
   } else {
     GemmParams p{};
     p.A = X; p.B = W; p.C = Y;
     p.M = s.n; p.N = s.d_out; p.K = s.d_in;
-    p.a_sm = s.ldx; p.a_sk = 1; p.b_sk = s.ldw; p.b_sn = 1; p.c_sm = s.ldy; p.c_sn = 1;
+    p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = s.ldy; p.c_sn = 1;
+    p.b_sk = w_oi ? 1 : s.ldw; p.b_sn = w_oi ? s.ldw : 1;
     p.k_per_split = round_up(s.d_in, 32);
     generic_gemm_io(desc->io_dtype, p, L);
   }
@@ -383,23 +393,35 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
 
   const SketchPlan sp_b = plan_sketch(desc, s.n, s.d_out, s.ldy);
   const bool fused_b = fused_ok(desc, sp_b, s.n, s.d_in, s.d_out, s.ldy, s.ldw);
-  // Gr[j, c] = sum_i S[i, j] dY[i, c]: the contraction of dY^T with S, stored transposed.  As in the
-  // forward pass the sketch goes first and leaves dY in the memory-side cache for the GEMM.
-  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, true, Gr, (float*)workspace, L);
+  // Gr[j, c] = sum_i S[i, j] dY[i, c]: the contraction of dY^T with S, stored transposed ([r, d_out]), or
+  // as it comes ([d_out, r]) in the paper's orientation.  As in the forward pass the sketch goes first
+  // and leaves dY in the memory-side cache for the GEMM.
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L);
   if (fused_b) {
     // W is [N = d_in, K = d_out]; the sketched matrix dY is the GEMM's left operand
     fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, (float*)workspace, L);
   } else if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
-    fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);  // W is [N = d_in, K = d_out]
+    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);  // W is [K = d_out, N = d_in]
+    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);        // W is [N = d_in, K = d_out]
   } else {
     GemmParams p{};
     p.A = dY; p.B = W; p.C = dX;
     p.M = s.n; p.N = s.d_in; p.K = s.d_out;
-    p.a_sm = s.ldy; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.ldw; p.c_sm = s.ldx; p.c_sn = 1;
+    p.a_sm = s.ldy; p.a_sk = 1; p.c_sm = s.ldx; p.c_sn = 1;
+    p.b_sk = w_oi ? s.ldw : 1; p.b_sn = w_oi ? 1 : s.ldw;
     p.k_per_split = round_up(s.d_out, 32);
     generic_gemm_io(desc->io_dtype, p, L);
   }
-  if (dW) {
+  if (dW && w_oi) {
+    // dW [d_out, d_in] = Gr [d_out, r] . Xs^T: Xs [N = d_in, K = r] is the K-contiguous right operand
+    if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
+      if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L);
+      else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L);
+    } else {
+      generic_dw(desc, s, Xs, Gr, dW, L);
+    }
+  } else if (dW) {
     if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
       if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
       else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
@@ -407,6 +429,41 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
       generic_dw(desc, s, Xs, Gr, dW, L);
     }
   }
+  return L.status();
+}
+
+int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, void* workspace,
+                         size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (!dY || !dB) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(dB) || !aligned16(workspace)) return ACC_ERR_ALIGN;
+  if (!workspace || ws_bytes < workspace_bytes(desc, s, true)) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  // Row slabs: enough waves in flight to pull dY at memory speed (16 per work-group, about 16 rows each),
+  // few enough partials for one short final pass; the backward workspace holds at least 16 rows of
+  // d_out floats (r >= 16).
+  int64_t G = ceil_div(s.n, 256);
+  if (G > 64) G = 64;
+  const int64_t fit = (int64_t)(ws_bytes / ((size_t)s.d_out * sizeof(float)));
+  if (G > fit) G = fit;
+  const int64_t rows = ceil_div(s.n, G);
+  G = ceil_div(s.n, rows);
+  float* part = (float*)workspace;
+  const dim3 block(64 * kColsumWaves);
+  if (desc->io_dtype == ACC_BF16)
+    L(colsum_partial_kernel<bf16>, dim3((unsigned)ceil_div(s.d_out, 512), (unsigned)G), block, (const bf16*)dY,
+      s.n, s.d_out, s.ldy, rows, part);
+  else
+    L(colsum_partial_kernel<float>, dim3((unsigned)ceil_div(s.d_out, 256), (unsigned)G), block, (const float*)dY,
+      s.n, s.d_out, s.ldy, rows, part);
+  const unsigned blocks = (unsigned)ceil_div(s.d_out, 64);
+  if (desc->dw_dtype == ACC_BF16)
+    L(colsum_final_kernel<bf16>, dim3(blocks), dim3(256), (const float*)part, (int)G, s.d_out, (bf16*)dB);
+  else
+    L(colsum_final_kernel<float>, dim3(blocks), dim3(256), (const float*)part, (int)G, s.d_out, (float*)dB);
   return L.status();
 }
 

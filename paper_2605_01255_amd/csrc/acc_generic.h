@@ -147,6 +147,65 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
   for (int t = 0; t < 4; ++t) out[e + t] = from_f32<TO>(s[t]);
 }
 
+// Column sums over a slab of rows (bias gradient, proof of Thm 3.2.2, bias term):
+// part[g * C + c] = sum over rows i of slab g of A[i, c], fp32.  Grid (ceil(C / (64 * VEC)), G).
+// A work-group has 16 waves; a lane owns VEC consecutive columns (one 16-byte load per row); wave w takes
+// rows w, w + 16, ... of the slab in order, and the per-wave sums are added in a fixed order, so the
+// result does not depend on scheduling.  C % VEC == 0; rows are 16-byte aligned.
+constexpr int kColsumWaves = 16;
+template <typename T>
+__global__ __launch_bounds__(64 * kColsumWaves) void colsum_partial_kernel(const T* __restrict__ A, int64_t n,
+                                                                            int64_t C, int64_t lda,
+                                                                            int64_t rows_per_split,
+                                                                            float* __restrict__ part) {
+  constexpr int VEC = 16 / sizeof(T);
+  typedef T vecT __attribute__((ext_vector_type(VEC)));
+  __shared__ float red[kColsumWaves][64 * VEC];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = ((int64_t)blockIdx.x * 64 + lane) * VEC;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_split;
+  const int64_t r1 = r0 + rows_per_split < n ? r0 + rows_per_split : n;
+  float s[VEC];
+#pragma unroll
+  for (int t = 0; t < VEC; ++t) s[t] = 0.f;
+  if (c < C) {
+#pragma unroll 8
+    for (int64_t i = r0 + wave; i < r1; i += kColsumWaves) {
+      const vecT v = *(const vecT*)(A + i * lda + c);
+#pragma unroll
+      for (int t = 0; t < VEC; ++t) s[t] += to_f32(v[t]);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < VEC; ++t) red[wave][lane * VEC + t] = s[t];
+  __syncthreads();
+  for (int e = threadIdx.x; e < 64 * VEC; e += 64 * kColsumWaves) {
+    const int64_t col = (int64_t)blockIdx.x * 64 * VEC + e;
+    float sum = red[0][e];
+#pragma unroll
+    for (int w = 1; w < kColsumWaves; ++w) sum += red[w][e];
+    if (col < C) part[(int64_t)blockIdx.y * C + col] = sum;
+  }
+}
+
+// out[c] = sum_g part[g * C + c] for a short vector (C columns, G partials): a work-group owns 64
+// columns, its wave w adds partials w, w + 4, ... in order, then the four wave sums are added in order.
+template <typename TO>
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int G, int64_t C,
+                                                           TO* __restrict__ out) {
+  __shared__ float red[4][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  float s = 0.f;
+  if (c < C) {
+#pragma unroll 8
+    for (int g = wave; g < G; g += 4) s += part[(int64_t)g * C + c];
+  }
+  red[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0 && c < C) out[c] = from_f32<TO>(((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane]);
+}
+
 // Test hook kernels -----------------------------------------------------------------------
 __global__ __launch_bounds__(256) void philox_dump_kernel(uint32_t key0, uint32_t key1,
                                                           uint64_t row_offset, int64_t nq, int64_t r,

@@ -17,15 +17,20 @@ def tolerance(dtype_code):
 
 
 def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, row_offset=0,
-              pad=(0, 0, 0), flags=0, seed=None, device="cuda:0"):
-    """One forward + backward through acc_linear_fwd / acc_linear_bwd.  Returns float64 arrays."""
+              pad=(0, 0, 0), flags=0, seed=None, device="cuda:0", want_db=False):
+    """One forward + backward through acc_linear_fwd / acc_linear_bwd.  Returns float64 arrays.
+
+    With ACC_FLAG_W_OUT_IN in flags the weight goes in as [d_out, d_in] and Gr / dW come back in that
+    orientation ([d_out, r], [d_out, d_in]).  want_db adds "dB" from acc_linear_bias_grad."""
     import torch
     code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
     fcode = code if factor_dtype is None else factor_dtype
     dcode = code if dw_dtype is None else dw_dtype
     seed = lin.seed if seed is None else seed
     tdt = acc.torch_dtype(code)
-    ldx, ldw, ldy = lin.d_in + pad[0], lin.d_out + pad[1], lin.d_out + pad[2]
+    w_oi = bool(flags & acc.ACC_FLAG_W_OUT_IN)
+    w_host = np.ascontiguousarray(data["W"].T) if w_oi else data["W"]
+    ldx, ldw, ldy = lin.d_in + pad[0], w_host.shape[1] + pad[1], lin.d_out + pad[2]
 
     def padded(arr, ld):
         t = acc.to_device(arr, device)
@@ -36,7 +41,7 @@ def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, ro
         return buf, buf
 
     X, _ = padded(data["X"], ldx)
-    W, _ = padded(data["W"], ldw)
+    W, _ = padded(w_host, ldw)
     dY, _ = padded(data["dY"], ldy)
     desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
                          dw_dtype=dcode, row_offset=row_offset, ldx=ldx if pad[0] else 0,
@@ -44,18 +49,26 @@ def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, ro
     Y = torch.full((lin.n, ldy), 7.0, dtype=tdt, device=device)
     dX = torch.full((lin.n, ldx), 7.0, dtype=tdt, device=device)
     Xs = torch.full((lin.d_in, lin.r), 7.0, dtype=acc.torch_dtype(fcode), device=device)
-    Gr = torch.full((lin.r, lin.d_out), 7.0, dtype=acc.torch_dtype(fcode), device=device)
-    dW = torch.full((lin.d_in, lin.d_out), 7.0, dtype=acc.torch_dtype(dcode), device=device) if want_dw else None
+    gr_shape = (lin.d_out, lin.r) if w_oi else (lin.r, lin.d_out)
+    dw_shape = (lin.d_out, lin.d_in) if w_oi else (lin.d_in, lin.d_out)
+    Gr = torch.full(gr_shape, 7.0, dtype=acc.torch_dtype(fcode), device=device)
+    dW = torch.full(dw_shape, 7.0, dtype=acc.torch_dtype(dcode), device=device) if want_dw else None
     acc.acc_linear_fwd(desc, X, W, Y, Xs, acc.alloc_workspace(desc, False, device))
     bdesc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
                           dw_dtype=dcode, row_offset=row_offset, ldx=desc.ldx, ldw=desc.ldw, ldy=desc.ldy,
                           flags=flags & ~acc.ACC_FLAG_SKIP_SKETCH)
-    acc.acc_linear_bwd(bdesc, dY, W, Xs, dX, Gr, dW, acc.alloc_workspace(bdesc, True, device))
+    ws_b = acc.alloc_workspace(bdesc, True, device)
+    acc.acc_linear_bwd(bdesc, dY, W, Xs, dX, Gr, dW, ws_b)
+    if want_db:
+        dB = torch.full((lin.d_out,), 7.0, dtype=acc.torch_dtype(dcode), device=device)
+        acc.acc_linear_bias_grad(bdesc, dY, dB, ws_b)
     torch.cuda.synchronize()
     out = {"Y": acc.to_host_f64(Y), "Xs": acc.to_host_f64(Xs), "dX": acc.to_host_f64(dX),
            "Gr": acc.to_host_f64(Gr)}
     if want_dw:
         out["dW"] = acc.to_host_f64(dW)
+    if want_db:
+        out["dB"] = acc.to_host_f64(dB)
     # padding columns must be untouched
     if pad[2]:
         assert np.all(out["Y"][:, lin.d_out:] == 7.0)
@@ -66,15 +79,19 @@ def run_layer(acc, lin, data, factor_dtype=None, dw_dtype=None, want_dw=True, ro
     return out
 
 
-def run_oracle(lin, data, want_dw=True, row_offset=0, seed=None):
+def run_oracle(lin, data, want_dw=True, row_offset=0, seed=None, w_out_in=False, want_db=False):
     seed = lin.seed if seed is None else seed
     X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+    if w_out_in:
+        W = np.ascontiguousarray(W.T)
     S = orc.sketch_matrix(seed, lin.n, lin.r, row_offset)
-    Y, Xs = orc.linear_fwd(X, W, S=S)
-    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=S, want_dW=want_dw)
+    Y, Xs = orc.linear_fwd(X, W, S=S, w_out_in=w_out_in)
+    dX, Gr, dW = orc.linear_bwd(dY, W, Xs, S=S, want_dW=want_dw, w_out_in=w_out_in)
     out = {"Y": Y, "Xs": Xs, "dX": dX, "Gr": Gr}
     if want_dw:
         out["dW"] = dW
+    if want_db:
+        out["dB"] = orc.bias_grad(dY)
     return out
 
 

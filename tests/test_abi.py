@@ -109,3 +109,25 @@ def test_workspace_query_is_positive_and_monotone_in_rank():
     a = acc.acc_linear_workspace_bytes(acc.make_desc(16384, 3072, 3072, 64), False)
     b = acc.acc_linear_workspace_bytes(acc.make_desc(16384, 3072, 3072, 256), False)
     assert 0 < a <= b
+
+
+def test_weight_orientation_flag_changes_the_row_length_of_w():
+    ok = dict(n=256, d_in=256, d_out=512, r=16)
+    # default orientation: a row of W holds d_out elements; with the flag, d_in
+    assert _fwd(acc.make_desc(**ok, ldw=256)) == -2
+    assert _fwd(acc.make_desc(**ok, ldw=256, flags=acc.ACC_FLAG_W_OUT_IN)) in (0, -6)
+    assert _fwd(acc.make_desc(**ok, ldw=248, flags=acc.ACC_FLAG_W_OUT_IN)) == -2
+    assert _bwd(acc.make_desc(**ok, ldw=248, flags=acc.ACC_FLAG_W_OUT_IN)) == -2
+
+
+def test_bias_gradient_refuses_bad_arguments():
+    d = acc.make_desc(n=256, d_in=256, d_out=512, r=16)
+    f = acc._lib.acc_linear_bias_grad
+    need = acc.acc_linear_workspace_bytes(d, True)
+    assert f(None, 0x1000, 0x2000, 0x3000, need, None) == -1
+    assert f(ctypes.byref(d), None, 0x2000, 0x3000, need, None) == -1
+    assert f(ctypes.byref(d), 0x1000, None, 0x3000, need, None) == -1
+    assert f(ctypes.byref(d), 0x1004, 0x2000, 0x3000, need, None) == -3
+    assert f(ctypes.byref(d), 0x1000, 0x2000, None, need, None) == -5
+    assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, need - 1, None) == -5
+    assert f(ctypes.byref(acc.make_desc(n=0, d_in=256, d_out=512, r=16)), 0x1000, 0x2000, 0x3000, need, None) == -2

@@ -23,7 +23,8 @@ def acc():
 def _check(acc, lin, tol=None, **kw):
     data = inputs.make(lin)
     got = gu.run_layer(acc, lin, data, **kw)
-    okw = {k: kw[k] for k in ("want_dw", "row_offset", "seed") if k in kw}
+    okw = {k: kw[k] for k in ("want_dw", "row_offset", "seed", "want_db") if k in kw}
+    okw["w_out_in"] = bool(kw.get("flags", 0) & acc.ACC_FLAG_W_OUT_IN)
     want = gu.run_oracle(lin, data, **okw)
     code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
     tol = tol or gu.tolerance(code)
@@ -165,3 +166,43 @@ def test_one_launch_flag_gives_identical_results(acc):
     want = gu.run_oracle(lin, data)
     for k in want:
         assert gu.rel(one[k], want[k]) <= 1e-2, k
+
+
+# ---- the paper's weight orientation ([d_out, d_in], Def. 3.1) and the bias gradient ------------------
+@pytest.mark.parametrize("n,d_in,d_out,r,dtype", [
+    (130, 72, 40, 16, "f32"),          # generic kernels, float32
+    (777, 520, 264, 48, "bf16"),       # generic kernels, bfloat16
+    (1000, 512, 640, 128, "bf16"),     # tuned kernels, 128 x 128 tiles
+    (4100, 1024, 3080, 256, "bf16"),   # tuned kernels, 256 x 256 tiles, ragged M and N
+    (2500, 576, 1096, 64, "bf16"),     # 4-wave sketch tile
+])
+def test_weight_out_in_orientation_and_bias_gradient(acc, n, d_in, d_out, r, dtype):
+    lin = inputs.Linear(f"oi_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype=dtype)
+    got, want, _ = _check(acc, lin, flags=acc.ACC_FLAG_W_OUT_IN, want_db=True)
+    assert got["Gr"].shape == (d_out, r) and got["dW"].shape == (d_out, d_in) and got["dB"].shape == (d_out,)
+    # same layer in the default orientation: exact products bit for bit, factors transposed bit for bit
+    ref = gu.run_layer(acc, lin, inputs.make(lin))
+    assert np.array_equal(got["Y"], ref["Y"]) and np.array_equal(got["dX"], ref["dX"])
+    assert np.array_equal(got["Xs"], ref["Xs"]) and np.array_equal(got["Gr"], ref["Gr"].T)
+
+
+def test_weight_out_in_with_strides_and_fp32_dw(acc):
+    lin = inputs.Linear("oi_strided", 1500, 512, 768, 128, dtype="bf16")
+    _check(acc, lin, flags=acc.ACC_FLAG_W_OUT_IN, dw_dtype=0, pad=(64, 8, 72), row_offset=4 * 77,
+           seed=0xABCDEF0123, want_db=True)
+
+
+@pytest.mark.parametrize("n,d_out,dtype", [(1, 8, "bf16"), (5, 24, "f32"), (1000, 520, "bf16"),
+                                           (16384, 3072, "bf16"), (4099, 264, "f32")])
+def test_bias_gradient_shapes(acc, n, d_out, dtype):
+    """dB = column sums of dY, fp32 accumulation; bitwise reproducible."""
+    lin = inputs.Linear(f"db_{n}x{d_out}", n, 16, d_out, 16, dtype=dtype)
+    data = inputs.make(lin)
+    a = gu.run_layer(acc, lin, data, want_dw=False, want_db=True, dw_dtype=0)
+    b = gu.run_layer(acc, lin, data, want_dw=False, want_db=True, dw_dtype=0)
+    want = orc.bias_grad(inputs.as_f64(data["dY"]))
+    assert np.array_equal(a["dB"], b["dB"])
+    # fp32 summation in a fixed tree: at most 16 rows per wave, 16 waves, then 16 + 4 partials -> at most
+    # 50 additions on any path for n <= 16384, so |error| <= 50 * 2^-24 * sum|dY| < 1e-5 * sum|dY| per column
+    scale = np.sum(np.abs(inputs.as_f64(data["dY"])), axis=0)
+    assert np.all(np.abs(a["dB"] - want) <= 1e-5 * scale + 1e-30), np.max(np.abs(a["dB"] - want) / (scale + 1e-30))
