@@ -101,7 +101,7 @@ def main():
     cfg, _, which = args.config.partition(".")
     linears = inputs.config(cfg)
     if which:
-        linears = [l for l in linears if l.name == args.config]
+        linears = [l for l in linears if l.name in (args.config, which)]
     with_dw = not args.no_dw
     lin = linears[0]                       # the benchmark line is quoted on the first linear of the config
     data = inputs.make(lin)

@@ -205,19 +205,35 @@ bool fast_gemm_ok(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb) {
          (N > K ? N : K) * ldb * 2 <= kMaxOperandBytes && 256 * lda * 2 <= kMaxOperandBytes;
 }
 
+// The K4 reduction of a sketch, handed to the GEMM launched right after it (FastGemmParams::red_*)
+// instead of taking a launch of its own.  count == 0: nothing pending.
+struct ReduceJob {
+  const float* part;
+  void* out;
+  int64_t count;
+  int G;
+  int out_bf16;
+};
+
 template <bool KMAJ, typename TC>
 void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda,
-               int64_t ldb, int64_t ldc, Launcher& L) {
+               int64_t ldb, int64_t ldc, Launcher& L, const ReduceJob* job = nullptr) {
   FastGemmParams p{};
   p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  if (job && job->count) {
+    p.red_part = job->part; p.red_out = job->out; p.red_count = job->count; p.red_G = job->G;
+    p.red_out_bf16 = job->out_bf16;
+  }
   const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
   if (big_tiles >= 192) {  // 256 x 256 tiles, 8 waves: enough tiles to fill 256 CUs
     const unsigned grid = gemm_bf16_plan(p, 256, 256);
+    p.red_stride = (int64_t)grid * 512 * 4;
     L.launch_lds(gemm_bf16_kernel<2, 4, 4, 2, KMAJ, TC>, dim3(grid), dim3(512),
                  (size_t)gemm_bf16_lds_bytes<2, 4, 4, 2>(), p);
   } else {                 // 128 x 128 tiles, 4 waves
     const unsigned grid = gemm_bf16_plan(p, 128, 128);
+    p.red_stride = (int64_t)grid * 256 * 4;
     L.launch_lds(gemm_bf16_kernel<2, 2, 2, 2, KMAJ, TC>, dim3(grid), dim3(256),
                  (size_t)gemm_bf16_lds_bytes<2, 2, 2, 2>(), p);
   }
@@ -264,7 +280,7 @@ void reduce_partials(const acc_linear_desc* d, const float* ws, int G, int64_t c
 
 // partial[g] (final orientation) with the tuned kernel, then K4 into `out`.
 void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, int64_t lda, int64_t channels,
-                 int64_t n, bool transposed, void* out, float* ws, Launcher& L) {
+                 int64_t n, bool transposed, void* out, float* ws, Launcher& L, ReduceJob* defer) {
   SketchFastParams p{};
   p.A = (const bf16*)A; p.part = ws; p.n = n; p.C = channels; p.lda = lda; p.r = (int)d->r;
   p.tokens_per_split = sp.tokens_per_split; p.n_cslab = sp.n_cslab; p.n_js = sp.n_js; p.G = sp.G;
@@ -279,7 +295,8 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
     if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true>, grid, dim3(256), lds, p);
     else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false>, grid, dim3(256), lds, p);
   }
-  reduce_partials(d, ws, sp.G, channels * d->r, out, L);
+  if (defer) *defer = ReduceJob{ws, out, channels * d->r, sp.G, d->factor_dtype == ACC_BF16 ? 1 : 0};
+  else reduce_partials(d, ws, sp.G, channels * d->r, out, L);
 }
 
 // One launch for the exact GEMM and the sketch of the same input (see acc_fused.h), then K4.
@@ -313,10 +330,12 @@ void fused_pass(const acc_linear_desc* d, const SketchPlan& sp, const void* A, c
   reduce_partials(d, ws, sp.G, K * d->r, factor_out, L);
 }
 
+// defer != nullptr: the caller launches a tuned GEMM next and wants it to fold the partials; the job is
+// filled in when the tuned sketch ran (its partials are pending), left empty otherwise.
 void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
-                bool transposed, void* out, float* ws, Launcher& L) {
+                bool transposed, void* out, float* ws, Launcher& L, ReduceJob* defer = nullptr) {
   const SketchPlan sp = plan_sketch(d, n, channels, lda);
-  if (sp.fast) fast_sketch(d, sp, A, lda, channels, n, transposed, out, ws, L);
+  if (sp.fast) fast_sketch(d, sp, A, lda, channels, n, transposed, out, ws, L, defer);
   else if (transposed) generic_sketch(d, A, lda, channels, n, 1, channels, out, ws, L);
   else generic_sketch(d, A, lda, channels, n, d->r, 1, out, ws, L);
 }
@@ -360,11 +379,13 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
   }
   // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
   // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
-  if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L);
+  const bool tuned_gemm = desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw);
+  ReduceJob job{};  // with a tuned GEMM next, the sketch leaves its K4 reduction to that launch
+  if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L, tuned_gemm ? &job : nullptr);
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W is [N = d_out, K = d_in]
-  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
-    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
-    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+  if (tuned_gemm) {
+    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, &job);
+    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, &job);
   } else {
     GemmParams p{};
     p.A = X; p.B = W; p.C = Y;
@@ -397,13 +418,15 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
   // as it comes ([d_out, r]) in the paper's orientation.  As in the forward pass the sketch goes first
   // and leaves dY in the memory-side cache for the GEMM.
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L);
+  const bool tuned_gemm = desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw);
+  ReduceJob job{};
+  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L, tuned_gemm ? &job : nullptr);
   if (fused_b) {
     // W is [N = d_in, K = d_out]; the sketched matrix dY is the GEMM's left operand
     fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, (float*)workspace, L);
-  } else if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
-    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);  // W is [K = d_out, N = d_in]
-    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);        // W is [N = d_in, K = d_out]
+  } else if (tuned_gemm) {
+    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, &job);  // W is [K = d_out, N = d_in]
+    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, &job);        // W is [N = d_in, K = d_out]
   } else {
     GemmParams p{};
     p.A = dY; p.B = W; p.C = dX;

@@ -27,6 +27,16 @@ struct FastGemmParams {
   int tiles_m, tiles_n;   // work-group tiles along M and N
   int super_m, super_n;   // XCD super-tile shape (in tiles), super_m * super_n == 32
   int supers_n;           // super-tiles along N
+  // Optional side job, done while the first tile's transfers are in flight: the reduction of the
+  // split-token partials a sketch kernel left just before this launch,
+  // red_out[e] = sum_g red_part[g * red_count + e] (same order as reduce_partials_kernel, so the same
+  // bits).  red_count == 0: none.  red_count % 4 == 0.
+  const float* red_part;
+  void* red_out;
+  int64_t red_count;
+  int64_t red_stride;     // elements all work-groups of the launch cover per sweep: grid * threads * 4
+  int red_G;
+  int red_out_bf16;       // 1: red_out is bf16, 0: float
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -112,7 +122,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   static_assert(B_KMAJOR || (BN_CHUNKS >= 16 && 64 % BN_CHUNKS == 0), "B tile shape");
 
   int tm, tn;
-  if (!xcd_tile(p, b, tm, tn)) return;
+  const bool has_tile = xcd_tile(p, b, tm, tn);
+  if (!has_tile && p.red_count == 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
@@ -240,7 +251,22 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
 
   // prologue: tile 0 -> stage 0, operands of its first k-step -> registers
   const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;  // LDS byte address of the dynamic segment
-  issue_loads(0, smem_lds);
+  if (has_tile) issue_loads(0, smem_lds);
+  if (p.red_count) {  // side job: this work-group's share of the partial sums, 4 elements per lane
+    for (int64_t e = ((int64_t)b * (NW * 64) + tid) * 4; e < p.red_count; e += p.red_stride) {
+      f32x4 sum = *(const f32x4*)(p.red_part + e);
+      for (int g = 1; g < p.red_G; ++g) sum += *(const f32x4*)(p.red_part + (int64_t)g * p.red_count + e);
+      if (p.red_out_bf16) {
+        bf16x4 v;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = (bf16)sum[t];
+        *(bf16x4*)((bf16*)p.red_out + e) = v;
+      } else {
+        *(f32x4*)((float*)p.red_out + e) = sum;
+      }
+    }
+    if (!has_tile) return;
+  }
   wait_vmcnt0();
   __syncthreads();
 #pragma unroll
