@@ -148,6 +148,14 @@ def main():
     # per-phase event timings (same launches, HIP events on the launch stream)
     ms_fwd = time_events(torch, fwd, args.steps)
     ms_bwd = time_events(torch, bwd, args.steps)
+    # the same step with the weight gradient left in factored form (no dense dW)
+    ms_bwd_nodw = None
+    if with_dw:
+        def bwd_nodw(i):
+            b = sets[i % len(sets)]
+            acc.acc_linear_bwd(desc, b.dY, b.W, b.Xs, b.dX, b.Gr, None, ws_b)
+        bwd_nodw(0)
+        ms_bwd_nodw = time_events(torch, bwd_nodw, args.steps)
     # dominant kernel: the exact-output GEMM Y = X.W, launched alone by a forward with the
     # sketch skipped (that call enqueues exactly one kernel)
     desc_gemm = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code,
@@ -180,6 +188,9 @@ def main():
                    "with_dw": with_dw, "buffer_sets": len(sets)},
         "pct_of_bf16_mfma_peak": round(100.0 * value / peak, 2),
         "ms_fwd": round(ms_fwd, 4), "ms_bwd": round(ms_bwd, 4),
+        "factored_only": None if ms_bwd_nodw is None else {
+            "ms_bwd": round(ms_bwd_nodw, 4),
+            "value": round(lin.flops(False) / ((ms_fwd + ms_bwd_nodw) * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},
         "activation_bytes_per_token": {"dense": dense_b / lin.n, "kept": round(kept_b / lin.n, 4),
                                        "saved": round((dense_b - kept_b) / lin.n, 4),
                                        "ratio": round(dense_b / kept_b, 2)},

@@ -63,9 +63,13 @@ enum {
                                 shape allows it (bf16, r % 128 == 0, >= 192 output tiles of
                                 256 x 256); otherwise ignored.  Results are identical; on
                                 MI355X the default (two launches) is measured ~5 % faster. */
-  ACC_FLAG_W_OUT_IN = 4u     /* W is [d_out, ldw >= d_in] (the layout of torch.nn.Linear.weight
+  ACC_FLAG_W_OUT_IN = 4u,    /* W is [d_out, ldw >= d_in] (the layout of torch.nn.Linear.weight
                                 and of the paper's Def. 3.1); Gr is then [d_out, r] and dW
                                 [d_out, d_in].  ACC_FLAG_ONE_LAUNCH is ignored with it.          */
+  ACC_FLAG_DW_ACCUMULATE = 8u /* backward only, with dW != NULL: dW += Xs.Gr, not dW = Xs.Gr
+                                (gradient accumulation over micro-batches on the dense gradient,
+                                Sec. 4 update strategy (i)).  A float dW is rounded once per call;
+                                a bfloat16 dW rounds the product and then the sum.               */
 };
 
 typedef struct acc_linear_desc {

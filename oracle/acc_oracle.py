@@ -129,8 +129,11 @@ def linear_fwd(X, W, seed: int = 0, r: int = 0, row_offset: int = 0, S=None, w_o
 
 
 def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None,
-               want_dW: bool = True, w_out_in: bool = False):
+               want_dW: bool = True, w_out_in: bool = False, dW_prev=None):
     """dX = dY W^T (exact), Gr = S^T dY, dW = Xs Gr (optional).
+
+    dW_prev: a dense gradient accumulated over earlier micro-batches (Sec. 4, update strategy (i):
+    the full gradient is reconstructed before the optimizer sees it); the new product is added to it.
 
     w_out_in: W is [d_out, d_in] and the gradient side follows the paper's orientation (Sec. 4):
     the factor is (grad_Z L)^T U = dY^T S, [d_out, r], and the weight gradient is
@@ -149,6 +152,8 @@ def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None
         dX = np.matmul(dY, W.T)
         Gr = np.matmul(S.T, dY)
         dW = np.matmul(Xs, Gr) if want_dW else None
+    if dW is not None and dW_prev is not None:
+        dW = np.asarray(dW_prev, dtype=np.float64) + dW
     return dX, Gr, dW
 
 

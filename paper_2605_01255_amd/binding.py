@@ -16,6 +16,7 @@ ACC_F32, ACC_BF16 = 0, 1
 ACC_FLAG_SKIP_SKETCH = 1
 ACC_FLAG_ONE_LAUNCH = 2
 ACC_FLAG_W_OUT_IN = 4
+ACC_FLAG_DW_ACCUMULATE = 8
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
            "acc_philox_dump_u32",

@@ -29,7 +29,7 @@ struct Shape {
 
 int validate_desc(const acc_linear_desc* d, Shape* s) {
   if (!d) return ACC_ERR_INVALID_ARG;
-  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN)) return ACC_ERR_INVALID_ARG;
+  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
@@ -189,6 +189,7 @@ void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const 
     p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
   }
   p.k_per_split = round_up(s.r, 32);
+  p.accumulate = (d->flags & ACC_FLAG_DW_ACCUMULATE) ? 1 : 0;
   const bool fb = d->factor_dtype == ACC_BF16, ob = d->dw_dtype == ACC_BF16;
   if (fb && ob) launch_generic<bf16, bf16, bf16, bf16, false, false>(p, 1, L);
   else if (fb) launch_generic<bf16, bf16, float, bf16, false, false>(p, 1, L);
@@ -217,8 +218,9 @@ struct ReduceJob {
 
 template <bool KMAJ, typename TC>
 void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda,
-               int64_t ldb, int64_t ldc, Launcher& L, const ReduceJob* job = nullptr) {
+               int64_t ldb, int64_t ldc, Launcher& L, const ReduceJob* job = nullptr, bool accumulate = false) {
   FastGemmParams p{};
+  p.accumulate = accumulate ? 1 : 0;
   p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   if (job && job->count) {
@@ -436,18 +438,19 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
     p.k_per_split = round_up(s.d_out, 32);
     generic_gemm_io(desc->io_dtype, p, L);
   }
+  const bool dw_acc = (desc->flags & ACC_FLAG_DW_ACCUMULATE) != 0;
   if (dW && w_oi) {
     // dW [d_out, d_in] = Gr [d_out, r] . Xs^T: Xs [N = d_in, K = r] is the K-contiguous right operand
     if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
-      if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L);
-      else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L);
+      if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
+      else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
     } else {
       generic_dw(desc, s, Xs, Gr, dW, L);
     }
   } else if (dW) {
     if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
-      if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
-      else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L);
+      if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
+      else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
     } else {
       generic_dw(desc, s, Xs, Gr, dW, L);
     }

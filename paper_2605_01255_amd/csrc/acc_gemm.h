@@ -37,6 +37,7 @@ struct FastGemmParams {
   int64_t red_stride;     // elements all work-groups of the launch cover per sweep: grid * threads * 4
   int red_G;
   int red_out_bf16;       // 1: red_out is bf16, 0: float
+  int accumulate;         // 1: C += A . B (a bf16 C rounds the product, then the sum), 0: C = A . B
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -255,6 +256,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   if (p.red_count) {  // side job: this work-group's share of the partial sums, 4 elements per lane
     for (int64_t e = ((int64_t)b * (NW * 64) + tid) * 4; e < p.red_count; e += p.red_stride) {
       f32x4 sum = *(const f32x4*)(p.red_part + e);
+#pragma unroll 8
       for (int g = 1; g < p.red_G; ++g) sum += *(const f32x4*)(p.red_part + (int64_t)g * p.red_count + e);
       if (p.red_out_bf16) {
         bf16x4 v;
@@ -332,7 +334,23 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       const u32x4 v = *(const u32x4*)(stage_w + row * PITCH + ch * 16);
       const int64_t gm = m0 + (wm * TM + i) * 32 + row;
       const int64_t gn = n0 + wn * TN * 32 + ch * (16 / ES);
-      if (gm < p.M && gn < p.N) *(u32x4*)(C + gm * p.ldc + gn) = v;
+      if (gm < p.M && gn < p.N) {
+        u32x4* dst = (u32x4*)(C + gm * p.ldc + gn);
+        if (p.accumulate) {
+          const u32x4 old = *dst;
+          if constexpr (ES == 2) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, v), o = __builtin_bit_cast(bf16x8, old);
+            bf16x8 sum;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) sum[t] = (bf16)((float)a[t] + (float)o[t]);
+            *dst = __builtin_bit_cast(u32x4, sum);
+          } else {
+            *dst = __builtin_bit_cast(u32x4, __builtin_bit_cast(f32x4, v) + __builtin_bit_cast(f32x4, old));
+          }
+        } else {
+          *dst = v;
+        }
+      }
     }
   }
 }

@@ -65,7 +65,7 @@ def test_invalid_descriptors_are_refused():
         assert acc.acc_linear_workspace_bytes(d, False) == 0
     assert _fwd(acc.make_desc(**ok, io_dtype=7)) == -4
     assert _fwd(acc.make_desc(**ok, factor_dtype=-1)) == -4
-    assert _fwd(acc.make_desc(**ok, flags=8)) == -1
+    assert _fwd(acc.make_desc(**ok, flags=16)) == -1
     assert _bwd(acc.make_desc(**ok, flags=acc.ACC_FLAG_SKIP_SKETCH)) == -1
     assert _fwd(acc.make_desc(**ok, flags=acc.ACC_FLAG_ONE_LAUNCH)) in (0, -6)
 

@@ -206,3 +206,39 @@ def test_bias_gradient_shapes(acc, n, d_out, dtype):
     # 50 additions on any path for n <= 16384, so |error| <= 50 * 2^-24 * sum|dY| < 1e-5 * sum|dY| per column
     scale = np.sum(np.abs(inputs.as_f64(data["dY"])), axis=0)
     assert np.all(np.abs(a["dB"] - want) <= 1e-5 * scale + 1e-30), np.max(np.abs(a["dB"] - want) / (scale + 1e-30))
+
+
+@pytest.mark.parametrize("dw_dtype,shape", [(0, (1000, 512, 640, 128)), (1, (1000, 512, 640, 128)),
+                                            (0, (130, 72, 40, 16)), (0, (4100, 1024, 3080, 256))])
+def test_dense_gradient_accumulates_over_micro_batches(acc, dw_dtype, shape):
+    """ACC_FLAG_DW_ACCUMULATE: two micro-batches (different data and seeds) summed into one dense dW."""
+    import torch
+    n, d_in, d_out, r = shape
+    dtype = "bf16" if d_in % 64 == 0 else "f32"
+    code = acc.ACC_BF16 if dtype == "bf16" else acc.ACC_F32
+    dcode = dw_dtype if dtype == "bf16" else acc.ACC_F32
+    dW = torch.zeros(d_in, d_out, dtype=acc.torch_dtype(dcode), device="cuda:0")
+    want = None
+    for mb, seed in enumerate((11, 12)):
+        lin = inputs.Linear(f"acc{mb}", n, d_in, d_out, r, dtype=dtype, seed=seed)
+        data = inputs.make(lin)
+        if mb:  # a different micro-batch: reverse the token order of the first one's data
+            data = {k: (np.ascontiguousarray(v[::-1]) if k in ("X", "dY") else v) for k, v in data.items()}
+        X, W, dY = (acc.to_device(data[k]) for k in ("X", "W", "dY"))
+        fd = acc.make_desc(n, d_in, d_out, r, seed=seed, io_dtype=code, dw_dtype=dcode)
+        bd = acc.make_desc(n, d_in, d_out, r, seed=seed, io_dtype=code, dw_dtype=dcode,
+                           flags=acc.ACC_FLAG_DW_ACCUMULATE if mb else 0)
+        Y = torch.empty(n, d_out, dtype=acc.torch_dtype(code), device="cuda:0")
+        dX = torch.empty(n, d_in, dtype=acc.torch_dtype(code), device="cuda:0")
+        Xs = torch.empty(d_in, r, dtype=acc.torch_dtype(code), device="cuda:0")
+        Gr = torch.empty(r, d_out, dtype=acc.torch_dtype(code), device="cuda:0")
+        acc.acc_linear_fwd(fd, X, W, Y, Xs, acc.alloc_workspace(fd, False))
+        acc.acc_linear_bwd(bd, dY, W, Xs, dX, Gr, dW, acc.alloc_workspace(bd, True))
+        Xf, Wf, dYf = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+        S = orc.sketch_matrix(seed, n, r)
+        _, Xs_o = orc.linear_fwd(Xf, Wf, S=S)
+        _, _, want = orc.linear_bwd(dYf, Wf, Xs_o, S=S, dW_prev=want)
+    torch.cuda.synchronize()
+    err = gu.rel(acc.to_host_f64(dW), want)
+    print("accumulated dW", err, flush=True)
+    assert err <= (1e-2 if dtype == "bf16" else 1e-5)   # bf16 factors bound the error even for a float dW

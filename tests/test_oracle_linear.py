@@ -174,3 +174,21 @@ def test_bias_gradient_is_the_derivative_of_the_affine_layer():
     Di = _ints(rng, (5, 3))
     assert orc.bias_grad(Di).tolist() == [sum(int(Di[i, o]) for i in range(5)) for o in range(3)]
     assert orc.bias_grad(np.zeros((0, 4))).tolist() == [0.0] * 4
+
+
+def test_accumulated_gradient_equals_the_product_of_stacked_factors():
+    """Two micro-batches accumulated on the dense gradient: dW_1 + dW_2 = [Xs_1 Xs_2] . [Gr_1; Gr_2],
+    the rank-2r factorisation of the summed estimate (Sec. 4), exact on integers."""
+    rng = np.random.default_rng(5)
+    d_in, d_out, r = 5, 4, 3
+    total = None
+    xs_all, gr_all = [], []
+    for n in (6, 9):
+        X, dY, S = _ints(rng, (n, d_in)), _ints(rng, (n, d_out)), _ints(rng, (n, r)).astype(np.float64)
+        W = _ints(rng, (d_in, d_out))
+        _, Xs = orc.linear_fwd(X, W, S=S)
+        _, Gr, total = orc.linear_bwd(dY, W, Xs, S=S, dW_prev=total)
+        xs_all.append(Xs); gr_all.append(Gr)
+    stacked = np.array(_loops_matmul(np.hstack(xs_all).astype(np.int64).tolist(),
+                                     np.vstack(gr_all).astype(np.int64).tolist()), dtype=np.float64)
+    assert np.array_equal(total, stacked)
