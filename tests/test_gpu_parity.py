@@ -242,3 +242,43 @@ def test_dense_gradient_accumulates_over_micro_batches(acc, dw_dtype, shape):
     err = gu.rel(acc.to_host_f64(dW), want)
     print("accumulated dW", err, flush=True)
     assert err <= (1e-2 if dtype == "bf16" else 1e-5)   # bf16 factors bound the error even for a float dW
+
+
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(acc):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so a
+    forward + backward + bias gradient can be captured once and replayed; every replay must reproduce the
+    eager result bit for bit, with eager work and synchronisations between replays."""
+    import torch
+    lin = inputs.Linear("graph", 4100, 1024, 3080, 256, dtype="bf16")
+    data = inputs.make(lin)
+    X, W, dY = (acc.to_device(data[k]) for k in ("X", "W", "dY"))
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=5, io_dtype=acc.ACC_BF16)
+    bf = torch.bfloat16
+    outs = {k: torch.empty(*shp, dtype=bf, device="cuda:0") for k, shp in
+            (("Y", (lin.n, lin.d_out)), ("dX", (lin.n, lin.d_in)), ("Xs", (lin.d_in, lin.r)),
+             ("Gr", (lin.r, lin.d_out)), ("dW", (lin.d_in, lin.d_out)), ("dB", (lin.d_out,)))}
+    ws_f, ws_b = acc.alloc_workspace(desc, False), acc.alloc_workspace(desc, True)
+
+    def enqueue():
+        acc.acc_linear_fwd(desc, X, W, outs["Y"], outs["Xs"], ws_f)
+        acc.acc_linear_bwd(desc, dY, W, outs["Xs"], outs["dX"], outs["Gr"], outs["dW"], ws_b)
+        acc.acc_linear_bias_grad(desc, dY, outs["dB"], ws_b)
+
+    enqueue()                      # eager: also raises the kernels' LDS limits outside the capture
+    torch.cuda.synchronize()
+    eager = {k: v.clone() for k, v in outs.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for v in outs.values():
+            v.fill_(3.0)           # eager work between replays; also proves the replay rewrites everything
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(outs[k], eager[k]), (rep, k)
