@@ -35,7 +35,9 @@ loops; exactness with an orthogonal S at r = n; Monte-Carlo unbiasedness
 (Thm 3.2.1(a)); the Gaussian-sketch variance closed form (Thm 3.3.1 per-layer
 term); the 1/sqrt(r) error law matching the paper's RP error table; dX independent
 of seed and rank (Thm 3.2.2(a)); the bias gradient against a finite difference of the
-affine layer's loss; the [d_out, d_in] orientation against index loops in the paper's form.  No function here is "parity unpinned".
+affine layer's loss; the [d_out, d_in] orientation against index loops in the paper's form;
+the RSVD factors against exact-fraction Gram-Schmidt, exact recovery of low-rank inputs, the
+Eckart-Young lower bound and the projection identities.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -154,6 +156,66 @@ def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None
         dW = np.matmul(Xs, Gr) if want_dW else None
     if dW is not None and dW_prev is not None:
         dW = np.asarray(dW_prev, dtype=np.float64) + dW
+    return dX, Gr, dW
+
+
+# ---------------------------------------------------------------------------------------------
+# RSVD compressor (Experimental Setup: randomized SVD of Halko, Martinsson and Tropp; Sec. 4: the
+# compressed activation is stored as two factors, X^ = U V^T with U [n, k] and V [d_in, k]).
+# The paper gives no parameters beyond the rank; the reading used here is the basic randomized range
+# finder followed by the projection onto it, with no oversampling, no power iteration and no final
+# rotation to singular vectors (a rotation inside the k-dimensional subspace changes neither X^ nor
+# the gradient estimate):
+#   Omega [d_in, k] Gaussian (same Philox map as S, the channel index in place of the token index),
+#   Yr = X Omega,  Yr = U R with U^T U = I and diag(R) > 0 (thin QR, unique for full column rank),
+#   V = X^T U,     X^ = U V^T = U U^T X,
+#   Gr = U^T dY,   dW = V Gr = X^^T dY.
+# Unlike S S^T X this estimator is a projection, not unbiased; its error is bounded below by the
+# best rank-k approximation error.
+# ---------------------------------------------------------------------------------------------
+def range_finder_matrix(seed: int, d_in: int, k: int):
+    """Omega [d_in, k]: i.i.d. normals addressed by (seed, channel, column); the scale is irrelevant."""
+    return sketch_matrix(seed, d_in, k, 0)
+
+
+def orthonormal_basis(Yr):
+    """Thin QR with positive diagonal of R (numpy's Householder QR as the library step, signs fixed)."""
+    Q, R = np.linalg.qr(np.asarray(Yr, dtype=np.float64), mode="reduced")
+    sign = np.where(np.diag(R) < 0, -1.0, 1.0)
+    return Q * sign[None, :], R * sign[:, None]
+
+
+def rsvd_factors(X, seed: int, k: int, Omega=None):
+    """U [n, k], V [d_in, k] of the RSVD-compressed activation X^ = U V^T."""
+    X = np.asarray(X, dtype=np.float64)
+    if Omega is None:
+        Omega = range_finder_matrix(seed, X.shape[1], k)
+    U, _ = orthonormal_basis(np.matmul(X, Omega))
+    V = np.matmul(X.T, U)
+    return U, V
+
+
+def linear_fwd_rsvd(X, W, seed: int = 0, k: int = 0, Omega=None, w_out_in: bool = False):
+    """Y = X W (exact) and the stored factors U, V of the RSVD-compressed input."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    Y = np.matmul(X, W.T) if w_out_in else np.matmul(X, W)
+    U, V = rsvd_factors(X, seed, k, Omega)
+    return Y, U, V
+
+
+def linear_bwd_rsvd(dY, W, U, V, want_dW: bool = True, w_out_in: bool = False):
+    """dX = dY W^T (exact), Gr = U^T dY [k, d_out], dW = V Gr (Sec. 4: ((grad_Z L)^T U) V^T, transposed)."""
+    dY = np.asarray(dY, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    dX = np.matmul(dY, W) if w_out_in else np.matmul(dY, W.T)
+    Gr = np.matmul(U.T, dY)
+    dW = np.matmul(V, Gr) if want_dW else None
+    if w_out_in:
+        Gr = Gr.T
+        dW = dW.T if dW is not None else None
     return dX, Gr, dW
 
 
