@@ -118,6 +118,32 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
 int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, void* workspace,
                          size_t ws_bytes, void* stream);
 
+/* ---- RSVD compressor (Experimental Setup: randomized SVD of Halko, Martinsson and Tropp; Sec. 4: the
+ * compressed activation is kept as two factors, X^ = U.V^T, U [n, r], V [d_in, r]) -------------------
+ * Reading (the paper fixes only the rank): randomized range finder and projection, no oversampling, no
+ * power iteration, no final rotation to singular vectors:
+ *   Omega [d_in, r] Gaussian, Omega[c, j] = the Philox normal of (seed, token index := c, column j);
+ *   Yr = X.Omega;  Yr = U.R, U^T.U = I, diag(R) > 0 (Cholesky QR, applied twice);  V = X^T.U.
+ * Here desc->r is the rank: multiple of 8, 8 <= r <= 128, r <= n, r <= d_in (else ACC_ERR_SHAPE);
+ * row_offset is ignored; ACC_FLAG_SKIP_SKETCH and ACC_FLAG_ONE_LAUNCH are refused.  If Yr has
+ * dependent columns (rank(X) < r) the corresponding columns of U and V are zero; U.V^T is still the
+ * projection of X onto the range of Yr.  U and V are stored as factor_dtype.                        */
+
+/* Bytes of device workspace of the RSVD forward (is_backward == 0) or backward call; 0 = invalid. */
+size_t acc_rsvd_workspace_bytes(const acc_linear_desc* desc, int is_backward);
+
+/* Forward with the RSVD compressor: Y = X.W exact (Def. 3.1), U [n, r] and V [d_in, r] (dense) are
+ * overwritten with the stored factors.  X [n, ldx], W are read. */
+int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* U, void* V,
+                        void* workspace, size_t ws_bytes, void* stream);
+
+/* Backward with stored RSVD factors (Sec. 4: the weight gradient is ((grad_Z L)^T.U).V^T): dX = dY.W^T
+ * exact, Gr = U^T.dY [r, d_out] ([d_out, r] with ACC_FLAG_W_OUT_IN) and, when dW != NULL,
+ * dW = V.Gr [d_in, d_out] (Gr.V^T [d_out, d_in] with ACC_FLAG_W_OUT_IN; += with ACC_FLAG_DW_ACCUMULATE).
+ * V may be NULL when dW is NULL. */
+int acc_linear_bwd_rsvd(const acc_linear_desc* desc, const void* dY, const void* W, const void* U, const void* V,
+                        void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream);
+
 /* Test hook: the Philox integer stream behind S.  out is a device array of
  * ceil(n/4) * r * 4 uint32 laid out [token group q][column j][word w]. */
 int acc_philox_dump_u32(uint64_t seed, uint64_t row_offset, int64_t n, int64_t r, uint32_t* out,

@@ -19,7 +19,7 @@ ACC_FLAG_W_OUT_IN = 4
 ACC_FLAG_DW_ACCUMULATE = 8
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
-           "acc_philox_dump_u32",
+           "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_philox_dump_u32",
            "acc_sketch_dump", "acc_status_string", "acc_version")
 
 
@@ -56,6 +56,12 @@ _lib.acc_linear_bwd.restype = ctypes.c_int
 _lib.acc_linear_bwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_linear_bias_grad.restype = ctypes.c_int
 _lib.acc_linear_bias_grad.argtypes = [_dp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_rsvd_workspace_bytes.restype = _sz
+_lib.acc_rsvd_workspace_bytes.argtypes = [_dp, ctypes.c_int]
+_lib.acc_linear_fwd_rsvd.restype = ctypes.c_int
+_lib.acc_linear_fwd_rsvd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_bwd_rsvd.restype = ctypes.c_int
+_lib.acc_linear_bwd_rsvd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_philox_dump_u32.restype = ctypes.c_int
 _lib.acc_philox_dump_u32.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64, _vp, _vp]
 _lib.acc_sketch_dump.restype = ctypes.c_int
@@ -135,6 +141,26 @@ def acc_linear_bias_grad(desc, dY, dB, workspace, stream=None, ws_bytes=None):
                                      _stream(stream)))
 
 
+def acc_rsvd_workspace_bytes(desc: AccLinearDesc, is_backward: bool) -> int:
+    return int(_lib.acc_rsvd_workspace_bytes(ctypes.byref(desc), 1 if is_backward else 0))
+
+
+def acc_linear_fwd_rsvd(desc, X, W, Y, U, V, workspace, stream=None, ws_bytes=None):
+    """Enqueue Y = X.W and the RSVD factors U [n, r], V [d_in, r] of X."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_linear_fwd_rsvd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(Y), _ptr(U), _ptr(V),
+                                    _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, dW, workspace, stream=None, ws_bytes=None):
+    """Enqueue dX = dY.W^T, Gr = U^T.dY and (dW is not None) dW = V.Gr."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_linear_bwd_rsvd(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(U), _ptr(V), _ptr(dX),
+                                    _ptr(Gr), _ptr(dW), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
 def acc_philox_dump_u32(seed, row_offset, n, r, out, stream=None):
     _check(_lib.acc_philox_dump_u32(seed, row_offset, n, r, _ptr(out), _stream(stream)))
 
@@ -166,7 +192,7 @@ def to_host_f64(t):
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
-def alloc_workspace(desc, is_backward: bool, device="cuda:0"):
+def alloc_workspace(desc, is_backward: bool, device="cuda:0", rsvd: bool = False):
     import torch
-    nbytes = acc_linear_workspace_bytes(desc, is_backward)
+    nbytes = (acc_rsvd_workspace_bytes if rsvd else acc_linear_workspace_bytes)(desc, is_backward)
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)

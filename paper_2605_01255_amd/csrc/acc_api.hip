@@ -12,6 +12,7 @@
 #include "acc_fused.h"
 #include "acc_gemm.h"
 #include "acc_generic.h"
+#include "acc_rsvd.h"
 #include "acc_sketch.h"
 
 namespace acc {
@@ -27,13 +28,13 @@ struct Shape {
   int64_t n, d_in, d_out, r, ldx, ldw, ldy;
 };
 
-int validate_desc(const acc_linear_desc* d, Shape* s) {
+int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16) {
   if (!d) return ACC_ERR_INVALID_ARG;
   if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
-  if (d->r % 16 || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;
+  if (d->r % r_multiple || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;
   if (d->n > (int64_t)1 << 40 || d->d_in > (1 << 21) || d->d_out > (1 << 21) || d->r > (1 << 16))
     return ACC_ERR_SHAPE;
   if (d->row_offset % 4) return ACC_ERR_SHAPE;
@@ -342,6 +343,153 @@ void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t ch
   else generic_sketch(d, A, lda, channels, n, d->r, 1, out, ws, L);
 }
 
+// ---- RSVD compressor ------------------------------------------------------------------------
+// Forward chain: Yr = X.Omega -> Cholesky QR twice -> U -> V = X^T.U; every product on the generic MFMA
+// kernel (fp32 matrix instructions wherever an fp32 operand is involved), K-splits reduced by K4.
+struct RsvdPlan {
+  int g_gram;   // token splits of the k x k Gram products
+  int g_fact;   // token splits of V = X^T.U (forward) or Gr = U^T.dY (backward)
+  size_t off_y0, off_q1, off_gram_part, off_gram, off_rinv, off_fact_part, total;  // byte offsets
+};
+
+RsvdPlan plan_rsvd(const Shape& s, bool backward) {
+  RsvdPlan pl{};
+  const int64_t k = s.r;
+  const int64_t channels = backward ? s.d_out : s.d_in;
+  pl.g_gram = generic_sketch_splits(s.n, k, k);
+  pl.g_fact = generic_sketch_splits(s.n, channels, k);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
+  if (!backward) {
+    pl.off_y0 = take((size_t)s.n * k * 4);
+    pl.off_q1 = take((size_t)s.n * k * 4);
+    pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
+    pl.off_gram = take((size_t)k * k * 4);
+    pl.off_rinv = take((size_t)k * k * 4);
+  }
+  pl.off_fact_part = take((size_t)pl.g_fact * channels * k * 4);
+  pl.total = off;
+  return pl;
+}
+
+// C[M, N] (+ splits) = A . B with element strides, operand types by dtype code; CT is bf16 only when
+// both operands are bf16.
+void rsvd_gemm(int a_dt, int b_dt, int c_dt, const GemmParams& p, int splits, Launcher& L) {
+  const bool ab = a_dt == ACC_BF16, bb = b_dt == ACC_BF16, cb = c_dt == ACC_BF16;
+  if (ab && bb && !cb) launch_generic<bf16, bf16, float, bf16, false, false>(p, splits, L);
+  else if (ab && !bb && !cb) launch_generic<bf16, float, float, float, false, true>(p, splits, L);
+  else if (!ab && bb && !cb) launch_generic<float, bf16, float, float, false, true>(p, splits, L);
+  else if (!ab && !bb && !cb) launch_generic<float, float, float, float, false, true>(p, splits, L);
+  else if (!ab && !bb && cb) launch_generic<float, float, bf16, float, false, true>(p, splits, L);
+  else L.err = hipErrorInvalidValue;  // not used by the chain
+}
+
+void reduce_to(int out_dt, const float* part, int G, int64_t count, void* out, Launcher& L) {
+  const unsigned blocks = (unsigned)ceil_div(count, 1024);
+  if (out_dt == ACC_BF16) L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), part, G, count, count, (bf16*)out);
+  else L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out);
+}
+
+// One Cholesky-QR pass: Qout [n, k] = Yin [n, k] . R^-1 with Yin^T.Yin = R^T.R.
+void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, const float* Yin, void* Qout, int q_dt,
+                      Launcher& L) {
+  const int64_t k = s.r;
+  float* gram_part = (float*)(ws + pl.off_gram_part);
+  float* gram = (float*)(ws + pl.off_gram);
+  float* rinv = (float*)(ws + pl.off_rinv);
+  GemmParams g{};
+  g.A = Yin; g.B = Yin; g.C = gram_part;
+  g.M = k; g.N = k; g.K = s.n;
+  g.a_sm = 1; g.a_sk = k; g.b_sk = k; g.b_sn = 1; g.c_sm = k; g.c_sn = 1;
+  g.k_per_split = round_up(ceil_div(s.n, pl.g_gram), 32);
+  g.c_split_stride = k * k;
+  const int splits = (int)ceil_div(s.n, g.k_per_split);
+  rsvd_gemm(ACC_F32, ACC_F32, ACC_F32, g, splits, L);
+  reduce_to(ACC_F32, gram_part, splits, k * k, gram, L);
+  L.launch_lds(chol_inverse_kernel, dim3(1), dim3(256), (size_t)k * k * sizeof(double), (const float*)gram, rinv,
+               (int)k);
+  GemmParams q{};
+  q.A = Yin; q.B = rinv; q.C = Qout;
+  q.M = s.n; q.N = k; q.K = k;
+  q.a_sm = k; q.a_sk = 1; q.b_sk = k; q.b_sn = 1; q.c_sm = k; q.c_sn = 1;
+  q.k_per_split = round_up(k, 32);
+  rsvd_gemm(ACC_F32, ACC_F32, q_dt, q, 1, L);
+}
+
+// out[channels, k] (or its transpose) = A^T . U over the token axis, A [n, lda]; splits reduced by K4.
+void rsvd_factor(const acc_linear_desc* d, const Shape& s, const RsvdPlan& pl, char* ws, const void* A,
+                 int64_t lda, int64_t channels, const void* U, bool transposed, void* out, Launcher& L) {
+  const int64_t k = s.r;
+  float* part = (float*)(ws + pl.off_fact_part);
+  GemmParams p{};
+  p.A = A; p.B = U; p.C = part;
+  p.M = channels; p.N = k; p.K = s.n;
+  p.a_sm = 1; p.a_sk = lda; p.b_sk = k; p.b_sn = 1;
+  p.c_sm = transposed ? 1 : k; p.c_sn = transposed ? channels : 1;
+  p.k_per_split = round_up(ceil_div(s.n, pl.g_fact), 32);
+  p.c_split_stride = channels * k;
+  const int splits = (int)ceil_div(s.n, p.k_per_split);
+  rsvd_gemm(d->io_dtype, d->factor_dtype, ACC_F32, p, splits, L);
+  reduce_to(d->factor_dtype, part, splits, channels * k, out, L);
+}
+
+// The exact products shared with the random-projection entry points.
+void exact_forward_gemm(const acc_linear_desc* desc, const Shape& s, const void* X, const void* W, void* Y,
+                        Launcher& L) {
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
+    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+  } else {
+    GemmParams p{};
+    p.A = X; p.B = W; p.C = Y;
+    p.M = s.n; p.N = s.d_out; p.K = s.d_in;
+    p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = s.ldy; p.c_sn = 1;
+    p.b_sk = w_oi ? 1 : s.ldw; p.b_sn = w_oi ? s.ldw : 1;
+    p.k_per_split = round_up(s.d_in, 32);
+    generic_gemm_io(desc->io_dtype, p, L);
+  }
+}
+void exact_backward_gemm(const acc_linear_desc* desc, const Shape& s, const void* dY, const void* W, void* dX,
+                         Launcher& L) {
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
+    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);
+    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);
+  } else {
+    GemmParams p{};
+    p.A = dY; p.B = W; p.C = dX;
+    p.M = s.n; p.N = s.d_in; p.K = s.d_out;
+    p.a_sm = s.ldy; p.a_sk = 1; p.c_sm = s.ldx; p.c_sn = 1;
+    p.b_sk = w_oi ? s.ldw : 1; p.b_sn = w_oi ? 1 : s.ldw;
+    p.k_per_split = round_up(s.d_out, 32);
+    generic_gemm_io(desc->io_dtype, p, L);
+  }
+}
+
+// dW = V . Gr (or Gr . V^T in the paper's orientation): the same product as the random-projection path's.
+void dense_dw(const acc_linear_desc* desc, const Shape& s, const void* Xs, const void* Gr, void* dW, Launcher& L) {
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  const bool dw_acc = (desc->flags & ACC_FLAG_DW_ACCUMULATE) != 0;
+  if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
+    if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
+    else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
+  } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
+    if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
+    else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
+  } else {
+    generic_dw(desc, s, Xs, Gr, dW, L);
+  }
+}
+
+int validate_rsvd(const acc_linear_desc* d, Shape* s) {
+  const int rc = validate_desc(d, s, 8);
+  if (rc != ACC_OK) return rc;
+  if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
+  if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
+  return ACC_OK;
+}
+
 size_t workspace_bytes(const acc_linear_desc* d, const Shape& s, bool backward) {
   const int64_t channels = backward ? s.d_out : s.d_in;
   const SketchPlan sp = plan_sketch(d, s.n, channels, backward ? s.ldy : s.ldx);
@@ -455,6 +603,71 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
       generic_dw(desc, s, Xs, Gr, dW, L);
     }
   }
+  return L.status();
+}
+
+size_t acc_rsvd_workspace_bytes(const acc_linear_desc* desc, int is_backward) {
+  Shape s;
+  if (validate_rsvd(desc, &s) != ACC_OK) return 0;
+  return plan_rsvd(s, is_backward != 0).total;
+}
+
+int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* U, void* V,
+                        void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_rsvd(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (!X || !W || !Y || !U || !V) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(U) || !aligned16(V) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  const RsvdPlan pl = plan_rsvd(s, false);
+  if (!workspace || ws_bytes < pl.total) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  char* ws = (char*)workspace;
+  float* y0 = (float*)(ws + pl.off_y0);
+  float* q1 = (float*)(ws + pl.off_q1);
+  const int64_t k = s.r;
+
+  // Yr = X . Omega, Omega[c, j] from the Philox map with the channel index in the token's place
+  GemmParams p{};
+  p.A = X; p.B = nullptr; p.C = y0;
+  p.M = s.n; p.N = k; p.K = s.d_in;
+  p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = k; p.c_sn = 1;
+  p.k_per_split = round_up(s.d_in, 32);
+  acc_linear_desc od = *desc;
+  od.row_offset = 0;
+  p.sk = make_sketch_params(&od);
+  if (desc->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, 1, L);
+  else launch_generic<float, float, float, float, true, true>(p, 1, L);
+  // Two Cholesky-QR passes: the second removes the loss of orthogonality of the first.
+  cholesky_qr_pass(s, pl, ws, y0, q1, ACC_F32, L);
+  cholesky_qr_pass(s, pl, ws, q1, U, desc->factor_dtype, L);
+  // V = X^T . U with U as stored (rounded to the factor type), so that U V^T is the projection the
+  // backward pass will use
+  rsvd_factor(desc, s, pl, ws, X, s.ldx, s.d_in, U, false, V, L);
+  exact_forward_gemm(desc, s, X, W, Y, L);
+  return L.status();
+}
+
+int acc_linear_bwd_rsvd(const acc_linear_desc* desc, const void* dY, const void* W, const void* U, const void* V,
+                        void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_rsvd(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (!dY || !W || !U || !dX || !Gr || (dW && !V)) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(W) || !aligned16(U) || !aligned16(V) || !aligned16(dX) || !aligned16(Gr) ||
+      !aligned16(dW) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  const RsvdPlan pl = plan_rsvd(s, true);
+  if (!workspace || ws_bytes < pl.total) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  // Gr = U^T . dY [k, d_out], or dY^T . U [d_out, k] in the paper's orientation
+  rsvd_factor(desc, s, pl, (char*)workspace, dY, s.ldy, s.d_out, U, !w_oi, Gr, L);
+  exact_backward_gemm(desc, s, dY, W, dX, L);
+  if (dW) dense_dw(desc, s, V, Gr, dW, L);
   return L.status();
 }
 

@@ -1,0 +1,133 @@
+"""RSVD compressor on the GPU vs the CPU fp64 oracle, through the C ABI.
+
+What is compared: the exact products Y and dX; the stored factors U (orthonormal basis of range(X.Omega),
+unique because the triangular factor has a positive diagonal) and V = X^T.U; the backward factor Gr and the
+dense dW; and the reconstruction U.V^T.  Tolerances: 1e-2 relative Frobenius for bfloat16 outputs (the
+spec bar); for float32 the basis inherits the conditioning of Yr = X.Omega (fp32 products, fp32
+normals accurate to 4e-6), so the bar is cond(Yr) * 1e-5, evaluated in the test from the oracle's Yr."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2605_01255_amd import inputs
+from oracle import acc_oracle as orc
+import gpu_util as gu
+
+
+@pytest.fixture(scope="module")
+def acc():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_01255_amd import binding
+    return binding
+
+
+def run_rsvd(acc, lin, data, flags=0, factor_dtype=None, dw_dtype=None, want_dw=True, seed=None):
+    import torch
+    dev = "cuda:0"
+    code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
+    fcode = code if factor_dtype is None else factor_dtype
+    dcode = code if dw_dtype is None else dw_dtype
+    seed = lin.seed if seed is None else seed
+    w_oi = bool(flags & acc.ACC_FLAG_W_OUT_IN)
+    X, dY = acc.to_device(data["X"], dev), acc.to_device(data["dY"], dev)
+    W = acc.to_device(np.ascontiguousarray(data["W"].T) if w_oi else data["W"], dev)
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
+                         dw_dtype=dcode, flags=flags)
+    tdt, fdt, ddt = acc.torch_dtype(code), acc.torch_dtype(fcode), acc.torch_dtype(dcode)
+    Y = torch.full((lin.n, lin.d_out), 7.0, dtype=tdt, device=dev)
+    dX = torch.full((lin.n, lin.d_in), 7.0, dtype=tdt, device=dev)
+    U = torch.full((lin.n, lin.r), 7.0, dtype=fdt, device=dev)
+    V = torch.full((lin.d_in, lin.r), 7.0, dtype=fdt, device=dev)
+    Gr = torch.full((lin.d_out, lin.r) if w_oi else (lin.r, lin.d_out), 7.0, dtype=fdt, device=dev)
+    dW = torch.full((lin.d_out, lin.d_in) if w_oi else (lin.d_in, lin.d_out), 7.0, dtype=ddt, device=dev) \
+        if want_dw else None
+    acc.acc_linear_fwd_rsvd(desc, X, W, Y, U, V, acc.alloc_workspace(desc, False, dev, rsvd=True))
+    acc.acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, dW, acc.alloc_workspace(desc, True, dev, rsvd=True))
+    torch.cuda.synchronize()
+    out = {k: acc.to_host_f64(v) for k, v in (("Y", Y), ("dX", dX), ("U", U), ("V", V), ("Gr", Gr))}
+    if want_dw:
+        out["dW"] = acc.to_host_f64(dW)
+    return out
+
+
+def oracle_rsvd(lin, data, seed=None, w_out_in=False):
+    seed = lin.seed if seed is None else seed
+    X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+    if w_out_in:
+        W = np.ascontiguousarray(W.T)
+    Y, U, V = orc.linear_fwd_rsvd(X, W, seed, lin.r, w_out_in=w_out_in)
+    dX, Gr, dW = orc.linear_bwd_rsvd(dY, W, U, V, w_out_in=w_out_in)
+    cond = np.linalg.cond(X @ orc.range_finder_matrix(seed, lin.d_in, lin.r))
+    return {"Y": Y, "dX": dX, "U": U, "V": V, "Gr": Gr, "dW": dW}, cond
+
+
+SHAPES = [
+    # n, d_in, d_out, rank, dtype
+    (130, 72, 40, 16, "f32"),
+    (515, 264, 136, 8, "f32"),
+    (777, 520, 264, 32, "bf16"),
+    (1000, 512, 640, 8, "bf16"),        # the paper's smallest rank
+    (4100, 1024, 3080, 64, "bf16"),     # tuned GEMMs for the exact products and dW
+    (2049, 1032, 1544, 128, "bf16"),    # largest rank, ragged everything
+]
+
+
+@pytest.mark.parametrize("n,d_in,d_out,k,dtype", SHAPES)
+def test_rsvd_layer_against_oracle(acc, n, d_in, d_out, k, dtype):
+    lin = inputs.Linear(f"rsvd_{n}x{d_in}x{d_out}_k{k}", n, d_in, d_out, k, dtype=dtype, seed=3)
+    data = inputs.make(lin)
+    got = run_rsvd(acc, lin, data)
+    want, cond = oracle_rsvd(lin, data)
+    tol = 1e-2 if dtype == "bf16" else max(1e-5, cond * 1e-5)
+    errs = {key: gu.rel(got[key], want[key]) for key in want}
+    errs["UVt"] = gu.rel(got["U"] @ got["V"].T, want["U"] @ want["V"].T)
+    errs["orth"] = float(np.linalg.norm(got["U"].T @ got["U"] - np.eye(k)) / np.sqrt(k))
+    print(lin.name, f"cond={cond:.1f}", " ".join(f"{a}={b:.2e}" for a, b in errs.items()), flush=True)
+    bad = {a: b for a, b in errs.items() if not b <= tol}
+    assert not bad, (tol, bad)
+
+
+def test_rsvd_paper_orientation_and_fp32_factors(acc):
+    lin = inputs.Linear("rsvd_oi", 1500, 512, 768, 32, dtype="bf16", seed=9)
+    data = inputs.make(lin)
+    got = run_rsvd(acc, lin, data, flags=acc.ACC_FLAG_W_OUT_IN, factor_dtype=0, dw_dtype=0)
+    want, _ = oracle_rsvd(lin, data, w_out_in=True)
+    assert got["Gr"].shape == (768, 32) and got["dW"].shape == (768, 512)
+    for key in want:
+        assert gu.rel(got[key], want[key]) <= 1e-2, key
+    ref = run_rsvd(acc, lin, data, factor_dtype=0, dw_dtype=0)
+    assert np.array_equal(got["U"], ref["U"]) and np.array_equal(got["V"], ref["V"])
+    assert np.array_equal(got["Y"], ref["Y"]) and np.array_equal(got["dX"], ref["dX"])
+    assert np.array_equal(got["Gr"], ref["Gr"].T)
+
+
+def test_rsvd_is_exact_for_low_rank_inputs_and_drops_dependent_columns(acc):
+    """rank(X) = 12 < k = 16: Yr has dependent columns; the library zeroes the surplus basis vectors and
+    U.V^T still reproduces X; the weight gradient equals X^T.dY (Sec. 4)."""
+    rng = np.random.default_rng(7)
+    n, d_in, d_out, k = 600, 128, 96, 16
+    X = (rng.standard_normal((n, 12)) @ rng.standard_normal((12, d_in))).astype(np.float32)
+    lin = inputs.Linear("rsvd_lowrank", n, d_in, d_out, k, dtype="f32", seed=1)
+    data = inputs.make(lin)
+    data["X"] = X
+    got = run_rsvd(acc, lin, data)
+    Xf, dYf = X.astype(np.float64), inputs.as_f64(data["dY"])
+    assert np.all(np.isfinite(got["U"])) and np.all(np.isfinite(got["V"]))
+    assert gu.rel(got["U"] @ got["V"].T, Xf) <= 1e-4
+    assert gu.rel(got["dW"], Xf.T @ dYf) <= 1e-4
+    zero_cols = int(np.sum(np.linalg.norm(got["U"], axis=0) == 0))
+    assert zero_cols == k - 12, zero_cols
+
+
+def test_rsvd_is_deterministic_and_seed_dependent(acc):
+    lin = inputs.Linear("rsvd_det", 900, 256, 128, 16, dtype="bf16", seed=5)
+    data = inputs.make(lin)
+    a, b = run_rsvd(acc, lin, data), run_rsvd(acc, lin, data)
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+    c = run_rsvd(acc, lin, data, seed=6)
+    assert np.array_equal(a["Y"], c["Y"]) and np.array_equal(a["dX"], c["dX"])   # exact products ignore the seed
+    assert not np.array_equal(a["U"], c["U"])
