@@ -220,7 +220,30 @@ def main():
 
     step_oi(0)
     ms_oi = time_events(torch, step_oi, args.steps)
+    # RSVD compressor at the paper's rank 32 on the same layer (U [n, 32] + V [d_in, 32] kept)
+    k_rsvd = 32
+    desc_rs = acc.make_desc(lin.n, lin.d_in, lin.d_out, k_rsvd, seed=lin.seed, io_dtype=code)
+    ws_rf = acc.alloc_workspace(desc_rs, False, dev, rsvd=True)
+    ws_rb = acc.alloc_workspace(desc_rs, True, dev, rsvd=True)
+    U_rs = torch.empty(lin.n, k_rsvd, dtype=tdt, device=dev)
+    V_rs = torch.empty(lin.d_in, k_rsvd, dtype=tdt, device=dev)
+    Gr_rs = torch.empty(k_rsvd, lin.d_out, dtype=tdt, device=dev)
+
+    def fwd_rsvd(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd_rsvd(desc_rs, b.X, b.W, b.Y, U_rs, V_rs, ws_rf)
+
+    def bwd_rsvd(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_bwd_rsvd(desc_rs, b.dY, b.W, U_rs, V_rs, b.dX, Gr_rs, b.dW, ws_rb)
+
+    fwd_rsvd(0); bwd_rsvd(0)
+    n_rs = max(5, args.steps // 4)
+    ms_rf = time_events(torch, fwd_rsvd, n_rs)
+    ms_rb = time_events(torch, bwd_rsvd, n_rs)
     out["widened"] = {
+        "rsvd_rank32": {"ms_fwd": round(ms_rf, 4), "ms_bwd": round(ms_rb, 4),
+                        "kept_bytes_per_token": round((lin.n + lin.d_in) * k_rsvd * 2 / lin.n, 2)},
         "bias_grad": {"ms": round(ms_db, 4), "bound": "hbm", "achieved": round(db_bytes / (ms_db * 1e-3) / 1e9, 1),
                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(db_bytes / (ms_db * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         "w_out_in": {"ms_per_step": round(ms_oi, 4), "value": round(flops / (ms_oi * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},

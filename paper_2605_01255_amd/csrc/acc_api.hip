@@ -242,6 +242,34 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
   }
 }
 
+// Skinny product through the tuned kernel, the K range split over groups of work-groups so that about
+// `wgs_wanted` of them run: part[s][M][ldc] = A[:, K range s] . B[K range s, :], fp32.  Returns the number
+// of splits.  kb_rows: rows of an N-contiguous B that exist (K may be A's zero-padded length).
+template <int WM, int WN, int TM, int TN, bool KMAJ>
+int fast_gemm_splitk(const void* A, const void* B, float* part, int64_t M, int64_t N, int64_t K, int64_t lda,
+                     int64_t ldb, int64_t ldc, int64_t kb_rows, int wgs_wanted, Launcher& L) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  FastGemmParams p{};
+  p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = part;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.kb_rows = kb_rows;
+  gemm_bf16_plan(p, BM, BN);  // tiles_m, tiles_n; the XCD super-tile order is not used with splits
+  const int64_t tiles = ceil_div(M, BM) * ceil_div(N, BN);
+  const unsigned tile_blocks = (unsigned)tiles;
+  int64_t splits = ceil_div(wgs_wanted, tiles);
+  if (splits > K / 256) splits = K / 256;  // at least four K tiles per work-group
+  if (splits < 1) splits = 1;
+  p.k_per_split = round_up(ceil_div(K, splits), 64);
+  splits = ceil_div(K, p.k_per_split);
+  p.tile_blocks = (int)tile_blocks;
+  p.c_split_stride = M * ldc;
+  L.launch_lds(gemm_bf16_kernel<WM, WN, TM, TN, KMAJ, float>, dim3(tile_blocks * (unsigned)splits), dim3(WM * WN * 64),
+               (size_t)gemm_bf16_lds_bytes<WM, WN, TM, TN>(), p);
+  return (int)splits;
+}
+constexpr int kSkinnyWgs = 1024;        // work-groups a skinny split-K product aims for
+constexpr int kSkinnyMaxSplits = 64;    // bound used to size the partial buffers
+
 // Plan of the tuned sketch kernel for `channels` columns of a [n, ld] matrix.
 struct SketchPlan {
   bool fast;
@@ -347,16 +375,31 @@ void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t ch
 // Forward chain: Yr = X.Omega -> Cholesky QR twice -> U -> V = X^T.U; every product on the generic MFMA
 // kernel (fp32 matrix instructions wherever an fp32 operand is involved), K-splits reduced by K4.
 struct RsvdPlan {
+  bool tuned;   // bf16 inputs and factors, sizes the tuned GEMM kernel takes: skinny products via split K
   int g_gram;   // token splits of the k x k Gram products
-  int g_fact;   // token splits of V = X^T.U (forward) or Gr = U^T.dY (backward)
-  size_t off_y0, off_q1, off_gram_part, off_gram, off_rinv, off_fact_part, total;  // byte offsets
+  int g_fact;   // token splits of V = X^T.U (forward) or Gr = U^T.dY (backward), generic path
+  int64_t n_pad;  // tokens rounded up to 64 (K padding of the products over tokens)
+  size_t off_y0, off_q1, off_gram_part, off_gram, off_rinv, off_fact_part;  // byte offsets
+  size_t off_omega, off_ut, off_yr_part, total;
 };
 
-RsvdPlan plan_rsvd(const Shape& s, bool backward) {
+// Upper bound of the splits fast_gemm_splitk picks.
+int64_t splitk_bound(int64_t tiles, int64_t K) {
+  int64_t splits = ceil_div(kSkinnyWgs, tiles);
+  if (splits > K / 256) splits = K / 256;
+  return splits < 1 ? 1 : splits;
+}
+
+RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
   RsvdPlan pl{};
   const int64_t k = s.r;
   const int64_t channels = backward ? s.d_out : s.d_in;
-  pl.g_gram = generic_sketch_splits(s.n, k, k);
+  const int64_t ld_in = backward ? s.ldy : s.ldx;
+  pl.n_pad = round_up(s.n, 64);
+  pl.tuned = d->io_dtype == ACC_BF16 && d->factor_dtype == ACC_BF16 && s.d_in % 64 == 0 && s.n >= 256 &&
+             s.n * ld_in * 2 <= kMaxOperandBytes && pl.n_pad * 2 * k * 4 <= kMaxOperandBytes;
+  pl.g_gram = (int)ceil_div(s.n, 64);   // one 64-row chunk per work-group where possible: a single load latency
+  if (pl.g_gram > 256) pl.g_gram = 256;
   pl.g_fact = generic_sketch_splits(s.n, channels, k);
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
@@ -367,7 +410,18 @@ RsvdPlan plan_rsvd(const Shape& s, bool backward) {
     pl.off_gram = take((size_t)k * k * 4);
     pl.off_rinv = take((size_t)k * k * 4);
   }
-  pl.off_fact_part = take((size_t)pl.g_fact * channels * k * 4);
+  if (pl.tuned) {
+    const int64_t fact_splits = splitk_bound(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad);
+    pl.off_fact_part = take((size_t)fact_splits * k * channels * 4);
+    pl.off_ut = take((size_t)k * pl.n_pad * 2);
+    if (!backward) {
+      const int64_t yr_splits = splitk_bound(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in);
+      pl.off_omega = take((size_t)2 * k * s.d_in * 2);
+      pl.off_yr_part = take((size_t)yr_splits * s.n * 2 * k * 4);
+    }
+  } else {
+    pl.off_fact_part = take((size_t)pl.g_fact * channels * k * 4);
+  }
   pl.total = off;
   return pl;
 }
@@ -390,30 +444,32 @@ void reduce_to(int out_dt, const float* part, int G, int64_t count, void* out, L
   else L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out);
 }
 
-// One Cholesky-QR pass: Qout [n, k] = Yin [n, k] . R^-1 with Yin^T.Yin = R^T.R.
-void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, const float* Yin, void* Qout, int q_dt,
-                      Launcher& L) {
+// One Cholesky-QR pass: Q = Yin . R^-1 with Yin^T.Yin = R^T.R.  Q goes to any of: Qf (fp32 [n, k]),
+// Qt (factor dtype [n, k]), Ut (bf16 [k, n_pad], zero-padded transpose).
+void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, const float* Yin, float* Qf, void* Qt, int qt_dt,
+                      bf16* Ut, Launcher& L) {
   const int64_t k = s.r;
   float* gram_part = (float*)(ws + pl.off_gram_part);
-  float* gram = (float*)(ws + pl.off_gram);
   float* rinv = (float*)(ws + pl.off_rinv);
-  GemmParams g{};
-  g.A = Yin; g.B = Yin; g.C = gram_part;
-  g.M = k; g.N = k; g.K = s.n;
-  g.a_sm = 1; g.a_sk = k; g.b_sk = k; g.b_sn = 1; g.c_sm = k; g.c_sn = 1;
-  g.k_per_split = round_up(ceil_div(s.n, pl.g_gram), 32);
-  g.c_split_stride = k * k;
-  const int splits = (int)ceil_div(s.n, g.k_per_split);
-  rsvd_gemm(ACC_F32, ACC_F32, ACC_F32, g, splits, L);
-  reduce_to(ACC_F32, gram_part, splits, k * k, gram, L);
-  L.launch_lds(chol_inverse_kernel, dim3(1), dim3(256), (size_t)k * k * sizeof(double), (const float*)gram, rinv,
-               (int)k);
-  GemmParams q{};
-  q.A = Yin; q.B = rinv; q.C = Qout;
-  q.M = s.n; q.N = k; q.K = k;
-  q.a_sm = k; q.a_sk = 1; q.b_sk = k; q.b_sn = 1; q.c_sm = k; q.c_sn = 1;
-  q.k_per_split = round_up(k, 32);
-  rsvd_gemm(ACC_F32, ACC_F32, q_dt, q, 1, L);
+  float* gram = (float*)(ws + pl.off_gram);
+  const int rows = (int)round_up(ceil_div(s.n, pl.g_gram), 64);
+  const int parts = (int)ceil_div(s.n, rows);
+  L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, s.n, (int)k, rows, gram_part);
+  L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, parts, k * k, gram);
+  if (k <= 32) L(chol_inverse_small_kernel<32, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
+  else if (k <= 64) L(chol_inverse_small_kernel<64, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
+  else L.launch_lds(chol_inverse_kernel, dim3(1), dim3(256), (size_t)k * k * sizeof(double), (const float*)gram, 1, rinv,
+                    (int)k);
+  const int64_t kp = round_up(k, 32);
+  const size_t lds = (size_t)(64 * (kp + 1) + kp * (kp % 64 == 0 ? kp + 32 : kp)) * sizeof(float);
+  const int64_t rows_out = Ut ? pl.n_pad : s.n;
+  const dim3 grid((unsigned)ceil_div(rows_out, 64));
+  if (qt_dt == ACC_BF16)
+    L.launch_lds(tall_times_small_kernel<bf16>, grid, dim3(256), lds, Yin, s.n, (int)k, (const float*)rinv, Qf, (bf16*)Qt,
+                 Ut, pl.n_pad, rows_out);
+  else
+    L.launch_lds(tall_times_small_kernel<float>, grid, dim3(256), lds, Yin, s.n, (int)k, (const float*)rinv, Qf,
+                 (float*)Qt, Ut, pl.n_pad, rows_out);
 }
 
 // out[channels, k] (or its transpose) = A^T . U over the token axis, A [n, lda]; splits reduced by K4.
@@ -431,6 +487,24 @@ void rsvd_factor(const acc_linear_desc* d, const Shape& s, const RsvdPlan& pl, c
   const int splits = (int)ceil_div(s.n, p.k_per_split);
   rsvd_gemm(d->io_dtype, d->factor_dtype, ACC_F32, p, splits, L);
   reduce_to(d->factor_dtype, part, splits, channels * k, out, L);
+}
+
+// Tuned form of rsvd_factor: Ut [k, n_pad] = U^T (zero-padded) in the workspace, then
+// [k, channels] = Ut . A over the token axis with the K range split, folded (and transposed back to
+// [channels, k] unless `transposed`) by one small kernel.
+void rsvd_factor_tuned(const acc_linear_desc* d, const Shape& s, const RsvdPlan& pl, char* ws, const void* A,
+                       int64_t lda, int64_t channels, const void* U, bool transposed, void* out, Launcher& L) {
+  const int64_t k = s.r;
+  bf16* ut = (bf16*)(ws + pl.off_ut);
+  float* part = (float*)(ws + pl.off_fact_part);
+  if (U)  // backward: rebuild the transpose from the stored factor; forward wrote it with the last QR pass
+    L(transpose_pad_kernel<bf16>, dim3((unsigned)ceil_div(pl.n_pad * k, 256)), dim3(256), (const bf16*)U, s.n, (int)k,
+      pl.n_pad, ut);
+  const int splits = fast_gemm_splitk<2, 2, 1, 2, false>(ut, A, part, k, channels, pl.n_pad, pl.n_pad, lda, channels,
+                                                       s.n, kSkinnyWgs, L);
+  const unsigned blocks = (unsigned)ceil_div(k * channels, 256);
+  if (transposed) L(reduce_store_kernel<bf16, false>, dim3(blocks), dim3(256), (const float*)part, splits, k, channels, (bf16*)out);
+  else L(reduce_store_kernel<bf16, true>, dim3(blocks), dim3(256), (const float*)part, splits, k, channels, (bf16*)out);
 }
 
 // The exact products shared with the random-projection entry points.
@@ -609,7 +683,7 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
 size_t acc_rsvd_workspace_bytes(const acc_linear_desc* desc, int is_backward) {
   Shape s;
   if (validate_rsvd(desc, &s) != ACC_OK) return 0;
-  return plan_rsvd(s, is_backward != 0).total;
+  return plan_rsvd(desc, s, is_backward != 0).total;
 }
 
 int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* U, void* V,
@@ -620,7 +694,7 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
   if (!X || !W || !Y || !U || !V) return ACC_ERR_INVALID_ARG;
   if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(U) || !aligned16(V) || !aligned16(workspace))
     return ACC_ERR_ALIGN;
-  const RsvdPlan pl = plan_rsvd(s, false);
+  const RsvdPlan pl = plan_rsvd(desc, s, false);
   if (!workspace || ws_bytes < pl.total) return ACC_ERR_WORKSPACE;
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
@@ -630,22 +704,35 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
   const int64_t k = s.r;
 
   // Yr = X . Omega, Omega[c, j] from the Philox map with the channel index in the token's place
-  GemmParams p{};
-  p.A = X; p.B = nullptr; p.C = y0;
-  p.M = s.n; p.N = k; p.K = s.d_in;
-  p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = k; p.c_sn = 1;
-  p.k_per_split = round_up(s.d_in, 32);
   acc_linear_desc od = *desc;
   od.row_offset = 0;
-  p.sk = make_sketch_params(&od);
-  if (desc->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, 1, L);
-  else launch_generic<float, float, float, float, true, true>(p, 1, L);
+  if (pl.tuned) {
+    // Omega as hi + lo bfloat16 parts, one split-K pass of the tuned kernel over X, halves and splits folded
+    bf16* omega = (bf16*)(ws + pl.off_omega);
+    float* yr_part = (float*)(ws + pl.off_yr_part);
+    L(omega_hilo_kernel, dim3((unsigned)ceil_div(s.d_in / 4 * k, 256)), dim3(256), make_sketch_params(&od), s.d_in,
+      (int)k, s.d_in, omega);
+    const int splits = fast_gemm_splitk<2, 2, 1, 1, true>(X, omega, yr_part, s.n, 2 * k, s.d_in, s.ldx, s.d_in, 2 * k,
+                                                        0, kSkinnyWgs, L);
+    L(combine_hilo_kernel, dim3((unsigned)ceil_div(s.n * k, 256)), dim3(256), (const float*)yr_part, splits, s.n, (int)k,
+      y0);
+  } else {
+    GemmParams p{};
+    p.A = X; p.B = nullptr; p.C = y0;
+    p.M = s.n; p.N = k; p.K = s.d_in;
+    p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = k; p.c_sn = 1;
+    p.k_per_split = round_up(s.d_in, 32);
+    p.sk = make_sketch_params(&od);
+    if (desc->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, 1, L);
+    else launch_generic<float, float, float, float, true, true>(p, 1, L);
+  }
   // Two Cholesky-QR passes: the second removes the loss of orthogonality of the first.
-  cholesky_qr_pass(s, pl, ws, y0, q1, ACC_F32, L);
-  cholesky_qr_pass(s, pl, ws, q1, U, desc->factor_dtype, L);
+  cholesky_qr_pass(s, pl, ws, y0, q1, nullptr, ACC_F32, nullptr, L);
+  cholesky_qr_pass(s, pl, ws, q1, nullptr, U, desc->factor_dtype, pl.tuned ? (bf16*)(ws + pl.off_ut) : nullptr, L);
   // V = X^T . U with U as stored (rounded to the factor type), so that U V^T is the projection the
   // backward pass will use
-  rsvd_factor(desc, s, pl, ws, X, s.ldx, s.d_in, U, false, V, L);
+  if (pl.tuned) rsvd_factor_tuned(desc, s, pl, ws, X, s.ldx, s.d_in, nullptr, false, V, L);
+  else rsvd_factor(desc, s, pl, ws, X, s.ldx, s.d_in, U, false, V, L);
   exact_forward_gemm(desc, s, X, W, Y, L);
   return L.status();
 }
@@ -659,13 +746,14 @@ int acc_linear_bwd_rsvd(const acc_linear_desc* desc, const void* dY, const void*
   if (!aligned16(dY) || !aligned16(W) || !aligned16(U) || !aligned16(V) || !aligned16(dX) || !aligned16(Gr) ||
       !aligned16(dW) || !aligned16(workspace))
     return ACC_ERR_ALIGN;
-  const RsvdPlan pl = plan_rsvd(s, true);
+  const RsvdPlan pl = plan_rsvd(desc, s, true);
   if (!workspace || ws_bytes < pl.total) return ACC_ERR_WORKSPACE;
   if ((rc = check_device()) != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
   // Gr = U^T . dY [k, d_out], or dY^T . U [d_out, k] in the paper's orientation
-  rsvd_factor(desc, s, pl, (char*)workspace, dY, s.ldy, s.d_out, U, !w_oi, Gr, L);
+  if (pl.tuned) rsvd_factor_tuned(desc, s, pl, (char*)workspace, dY, s.ldy, s.d_out, U, !w_oi, Gr, L);
+  else rsvd_factor(desc, s, pl, (char*)workspace, dY, s.ldy, s.d_out, U, !w_oi, Gr, L);
   exact_backward_gemm(desc, s, dY, W, dX, L);
   if (dW) dense_dw(desc, s, V, Gr, dW, L);
   return L.status();

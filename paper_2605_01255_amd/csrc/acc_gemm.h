@@ -38,6 +38,15 @@ struct FastGemmParams {
   int red_G;
   int red_out_bf16;       // 1: red_out is bf16, 0: float
   int accumulate;         // 1: C += A . B (a bf16 C rounds the product, then the sum), 0: C = A . B
+  // Optional split of the K range over work-groups (skinny products whose M x N tiles alone do not fill
+  // the chip): tile_blocks == 0 means no split.  Block b works on tile b % tile_blocks and K range
+  // [s * k_per_split, min(K, (s + 1) * k_per_split)), s = b / tile_blocks, and stores its partial product
+  // at C + s * c_split_stride.  k_per_split % 64 == 0.
+  int tile_blocks;
+  int64_t k_per_split;
+  int64_t c_split_stride;
+  int64_t kb_rows;        // N-contiguous B only: rows of B that exist (0 = K); K may exceed it when A is
+                          // zero-padded along K, the missing rows of B then read as zero
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -99,6 +108,11 @@ __device__ __forceinline__ void wait_vmcnt0() { asm volatile("s_waitcnt vmcnt(0)
 // (work-groups are dealt round-robin to the 8 XCDs) form a super_m x super_n block that shares
 // A and B panels in that XCD's L2.  Returns false for padding work-groups.
 __device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int b, int& tm, int& tn) {
+  if (p.tile_blocks) {  // split-K launches of skinny products: few tiles, plain order, no padding blocks
+    tm = b % p.tiles_m;
+    tn = b / p.tiles_m;
+    return tn < p.tiles_n;
+  }
   const int xcd = b & 7, local = b >> 3;
   const int sid = (local >> 5) * 8 + xcd;  // super-tile id, N fastest
   const int in = local & 31;
@@ -123,6 +137,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   static_assert(B_KMAJOR || (BN_CHUNKS >= 16 && 64 % BN_CHUNKS == 0), "B tile shape");
 
   int tm, tn;
+  int64_t k0 = 0, k1 = p.K;  // this work-group's K range
+  int split = 0;
+  if (p.tile_blocks) {
+    split = b / p.tile_blocks;
+    b -= split * p.tile_blocks;
+    k0 = (int64_t)split * p.k_per_split;
+    k1 = k0 + p.k_per_split < p.K ? k0 + p.k_per_split : p.K;
+  }
   const bool has_tile = xcd_tile(p, b, tm, tn);
   if (!has_tile && p.red_count == 0) return;
   const int tid = threadIdx.x, lane = tid & 63;
@@ -136,10 +158,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   // buffer resources that start at the tile's first row / column; rows past the end of the matrix
   // read as zero (their products are never stored).
   const int64_t am0 = m0, bn0 = n0;
-  const u32x4 a_rsrc = make_rsrc(p.A + am0 * p.lda, ((p.M - am0 - 1) * p.lda + p.K) * 2);
+  const int64_t kb = p.kb_rows ? p.kb_rows : p.K;
+  const u32x4 a_rsrc = make_rsrc(p.A + am0 * p.lda + k0, ((p.M - am0 - 1) * p.lda + p.K - k0) * 2);
   const u32x4 b_rsrc =
-      B_KMAJOR ? make_rsrc(p.B + bn0 * p.ldb, ((p.N - bn0 - 1) * p.ldb + p.K) * 2)
-               : make_rsrc(p.B + bn0, ((p.K - 1) * p.ldb + (p.N - bn0)) * 2);
+      B_KMAJOR ? make_rsrc(p.B + bn0 * p.ldb + k0, ((p.N - bn0 - 1) * p.ldb + p.K - k0) * 2)
+               : make_rsrc(p.B + k0 * p.ldb + bn0, kb > k0 ? ((kb - k0 - 1) * p.ldb + (p.N - bn0)) * 2 : 0);
   uint32_t a_src[A_LOADS];
 #pragma unroll
   for (int t = 0; t < A_LOADS; ++t) {
@@ -204,7 +227,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int KT = (int)(p.K / BK);
+  const int KT = (int)((k1 - k0) / BK);
   bf16x8 af[2][TM], bfr[2][TN];
 
   auto read_a1 = [&](const char* st, int s, int i, bf16x8(&dst)[TM]) {
@@ -242,10 +265,24 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       // B operand first: the product comes out transposed, lane = output row, 4 consecutive registers =
       // 4 consecutive output columns, which is what the epilogue packs
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
-      if (q < TM) read_a1(rd_stage, rd_s, q, na);
-      else if (q < TM + TN) read_b1(rd_stage, rd_s, q - TM, nb);
-      if (q % G_EVERY == 0 && q / G_EVERY < g_count && g_first + q / G_EVERY < NG_TOTAL)
-        issue_one(g_first + q / G_EVERY, kt_next, nxt);
+      if constexpr (NM >= TM + TN) {
+        if (q < TM) read_a1(rd_stage, rd_s, q, na);
+        else if (q < TM + TN) read_b1(rd_stage, rd_s, q - TM, nb);
+      } else {  // small tiles: fewer MFMAs than operand reads, several reads per MFMA
+#pragma unroll
+        for (int i = q; i < TM + TN; i += NM) {
+          if (i < TM) read_a1(rd_stage, rd_s, i, na);
+          else read_b1(rd_stage, rd_s, i - TM, nb);
+        }
+      }
+      if constexpr (NM < G_PER_STEP) {  // fewer MFMAs than wave-loads in a k-step: several loads per MFMA
+#pragma unroll
+        for (int i = q; i < G_PER_STEP; i += NM)
+          if (i < g_count && g_first + i < NG_TOTAL) issue_one(g_first + i, kt_next, nxt);
+      } else {
+        if (q % G_EVERY == 0 && q / G_EVERY < g_count && g_first + q / G_EVERY < NG_TOTAL)
+          issue_one(g_first + q / G_EVERY, kt_next, nxt);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -307,7 +344,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   static_assert(NW * WAVE_B <= 2 * STAGE, "epilogue staging exceeds the pipeline's LDS");
   __syncthreads();                               // every wave is done with the pipeline's LDS
   char* stage_w = smem + wave * WAVE_B;
-  TC* __restrict__ C = (TC*)p.C;
+  TC* __restrict__ C = (TC*)p.C + (int64_t)split * p.c_split_stride;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
