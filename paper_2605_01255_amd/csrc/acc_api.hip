@@ -508,12 +508,20 @@ void rsvd_factor_tuned(const acc_linear_desc* d, const Shape& s, const RsvdPlan&
 }
 
 // The exact products shared with the random-projection entry points.
+// Whether the exact product of a pass runs on the tuned kernel (and can fold a pending K4 reduction).
+bool forward_gemm_is_tuned(const acc_linear_desc* desc, const Shape& s) {
+  return desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw);
+}
+bool backward_gemm_is_tuned(const acc_linear_desc* desc, const Shape& s) {
+  return desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw);
+}
+
 void exact_forward_gemm(const acc_linear_desc* desc, const Shape& s, const void* X, const void* W, void* Y,
-                        Launcher& L) {
-  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
-    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
-    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L);
+                        Launcher& L, const ReduceJob* job = nullptr) {
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W is [N = d_out, K = d_in]
+  if (forward_gemm_is_tuned(desc, s)) {
+    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, job);
+    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, job);
   } else {
     GemmParams p{};
     p.A = X; p.B = W; p.C = Y;
@@ -525,11 +533,11 @@ void exact_forward_gemm(const acc_linear_desc* desc, const Shape& s, const void*
   }
 }
 void exact_backward_gemm(const acc_linear_desc* desc, const Shape& s, const void* dY, const void* W, void* dX,
-                         Launcher& L) {
+                         Launcher& L, const ReduceJob* job = nullptr) {
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  if (desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw)) {
-    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);
-    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L);
+  if (backward_gemm_is_tuned(desc, s)) {
+    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, job);  // W is [K = d_out, N = d_in]
+    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, job);        // W is [N = d_in, K = d_out]
   } else {
     GemmParams p{};
     p.A = dY; p.B = W; p.C = dX;
@@ -603,22 +611,11 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
   }
   // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
   // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
-  const bool tuned_gemm = desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw);
   ReduceJob job{};  // with a tuned GEMM next, the sketch leaves its K4 reduction to that launch
-  if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L, tuned_gemm ? &job : nullptr);
-  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W is [N = d_out, K = d_in]
-  if (tuned_gemm) {
-    if (w_oi) fast_gemm<true, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, &job);
-    else fast_gemm<false, bf16>(X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, L, &job);
-  } else {
-    GemmParams p{};
-    p.A = X; p.B = W; p.C = Y;
-    p.M = s.n; p.N = s.d_out; p.K = s.d_in;
-    p.a_sm = s.ldx; p.a_sk = 1; p.c_sm = s.ldy; p.c_sn = 1;
-    p.b_sk = w_oi ? 1 : s.ldw; p.b_sn = w_oi ? s.ldw : 1;
-    p.k_per_split = round_up(s.d_in, 32);
-    generic_gemm_io(desc->io_dtype, p, L);
-  }
+  if (sketch)
+    run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L,
+               forward_gemm_is_tuned(desc, s) ? &job : nullptr);
+  exact_forward_gemm(desc, s, X, W, Y, L, &job);
   return L.status();
 }
 
@@ -642,41 +639,16 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
   // as it comes ([d_out, r]) in the paper's orientation.  As in the forward pass the sketch goes first
   // and leaves dY in the memory-side cache for the GEMM.
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  const bool tuned_gemm = desc->io_dtype == ACC_BF16 && fast_gemm_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw);
-  ReduceJob job{};
-  if (!fused_b) run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L, tuned_gemm ? &job : nullptr);
   if (fused_b) {
     // W is [N = d_in, K = d_out]; the sketched matrix dY is the GEMM's left operand
     fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, (float*)workspace, L);
-  } else if (tuned_gemm) {
-    if (w_oi) fast_gemm<false, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, &job);  // W is [K = d_out, N = d_in]
-    else fast_gemm<true, bf16>(dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, L, &job);        // W is [N = d_in, K = d_out]
   } else {
-    GemmParams p{};
-    p.A = dY; p.B = W; p.C = dX;
-    p.M = s.n; p.N = s.d_in; p.K = s.d_out;
-    p.a_sm = s.ldy; p.a_sk = 1; p.c_sm = s.ldx; p.c_sn = 1;
-    p.b_sk = w_oi ? s.ldw : 1; p.b_sn = w_oi ? 1 : s.ldw;
-    p.k_per_split = round_up(s.d_out, 32);
-    generic_gemm_io(desc->io_dtype, p, L);
+    ReduceJob job{};
+    run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L,
+               backward_gemm_is_tuned(desc, s) ? &job : nullptr);
+    exact_backward_gemm(desc, s, dY, W, dX, L, &job);
   }
-  const bool dw_acc = (desc->flags & ACC_FLAG_DW_ACCUMULATE) != 0;
-  if (dW && w_oi) {
-    // dW [d_out, d_in] = Gr [d_out, r] . Xs^T: Xs [N = d_in, K = r] is the K-contiguous right operand
-    if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
-      if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
-      else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
-    } else {
-      generic_dw(desc, s, Xs, Gr, dW, L);
-    }
-  } else if (dW) {
-    if (desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
-      if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
-      else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
-    } else {
-      generic_dw(desc, s, Xs, Gr, dW, L);
-    }
-  }
+  if (dW) dense_dw(desc, s, Xs, Gr, dW, L);
   return L.status();
 }
 
