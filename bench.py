@@ -27,6 +27,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="c2", help="c1 | c2 | c3_r256 | c4 | c5 (a named linear: c4.k)")
+    ap.add_argument("--layer", default=None, help="c4 | c5: time all linears of a decoder layer instead (own JSON line)")
     ap.add_argument("--no-dw", action="store_true", help="leave the dense dW out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--buffer-sets", type=int, default=3, help="rotated so no tensor stays in the 256 MB cache")
@@ -62,6 +63,82 @@ def time_events(torch, fn, iters):
     e1.record(st)
     e1.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def time_each(torch, fn, iters):
+    """Milliseconds of every single call of fn(i), one pair of HIP events per call: (median, min)."""
+    st = torch.cuda.current_stream()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for i, (a, b) in enumerate(evs):
+        a.record(st)
+        fn(i)
+        b.record(st)
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], ts[0]
+
+
+def run_layer(args, torch, acc, inputs, dev):
+    """All linears of a decoder-layer configuration (c4, c5), the linears that share an input sketched once
+    (ACC_FLAG_SKIP_SKETCH on the others; Sec. 5.1: q/k/v see the same activation, so do gate/up).  Prints one
+    JSON line for the layer: algorithmic TFLOP/s over all linears and the activation bytes kept."""
+    linears = inputs.config(args.layer)
+    groups = {}                              # distinct input tensors: q,k,v | o | gate,up | down
+    for l in linears:
+        key = {"q": "attn_in", "k": "attn_in", "v": "attn_in", "gate": "mlp_in", "up": "mlp_in"}.get(
+            l.name.split(".")[-1], l.name)
+        groups.setdefault(key, []).append(l)
+    bf, items = torch.bfloat16, []
+    torch.manual_seed(inputs.DATA_SEED)      # dY is drawn on the device: N(0, 0.01^2), seeded
+    for key, ls in groups.items():
+        first = ls[0]
+        X = acc.to_device(inputs.store(inputs.make_x(first), first.dtype), dev)
+        Xs = torch.empty(first.d_in, first.r, dtype=bf, device=dev)
+        for i, l in enumerate(ls):
+            W = acc.to_device(inputs.store(inputs.make_w(l), l.dtype), dev)
+            dY = torch.randn(l.n, l.d_out, device=dev, dtype=torch.float32).mul_(0.01).to(bf)
+            fl = acc.ACC_FLAG_SKIP_SKETCH if i else 0
+            fd = acc.make_desc(l.n, l.d_in, l.d_out, l.r, seed=first.seed, flags=fl)
+            bd = acc.make_desc(l.n, l.d_in, l.d_out, l.r, seed=first.seed)
+            items.append(dict(l=l, X=X, W=W, dY=dY, Xs=Xs, fd=fd, bd=bd, sketch=(i == 0),
+                              Y=torch.empty(l.n, l.d_out, dtype=bf, device=dev),
+                              dX=torch.empty(l.n, l.d_in, dtype=bf, device=dev),
+                              Gr=torch.empty(l.r, l.d_out, dtype=bf, device=dev),
+                              dW=torch.empty(l.d_in, l.d_out, dtype=bf, device=dev),
+                              ws_f=acc.alloc_workspace(bd, False, dev), ws_b=acc.alloc_workspace(bd, True, dev)))
+
+    def step(_):
+        for it in items:
+            acc.acc_linear_fwd(it["fd"], it["X"], it["W"], it["Y"], it["Xs"], it["ws_f"] if it["sketch"] else None)
+        for it in reversed(items):
+            acc.acc_linear_bwd(it["bd"], it["dY"], it["W"], it["Xs"], it["dX"], it["Gr"], it["dW"], it["ws_b"])
+
+    steps, warm = max(3, args.steps // 5), max(1, args.warmup // 5)
+    for i in range(warm):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flops = 0
+    for it in items:
+        l = it["l"]
+        flops += 4 * l.n * l.d_in * l.d_out + 2 * l.n * l.r * l.d_out + 2 * l.d_in * l.r * l.d_out
+        if it["sketch"]:
+            flops += 2 * l.n * l.d_in * l.r
+    dense = sum(ls[0].n * ls[0].d_in * 2 for ls in groups.values())
+    kept = sum(ls[0].d_in * ls[0].r * 2 + 8 for ls in groups.values())
+    n = linears[0].n
+    print(json.dumps({
+        "metric": "compressed decoder-layer linears fwd+bwd TFLOP/s", "value": round(flops / (ms * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warm, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.layer}: {len(items)} linears, n={n}, shared sketches for q/k/v and gate/up",
+                   "with_dw": True},
+        "activation_bytes": {"dense_per_distinct_input": dense, "kept": kept, "ratio": round(dense / kept, 2),
+                             "dense_per_token": dense / n, "kept_per_token": round(kept / n, 3)}}), flush=True)
 
 
 def cpu_baseline(lin, data, with_dw, budget_tokens):
@@ -103,6 +180,9 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.layer:
+        run_layer(args, torch, acc, inputs, dev)
+        return
     cfg, _, which = args.config.partition(".")
     linears = inputs.config(cfg)
     if which:
@@ -150,6 +230,7 @@ def main():
     value = flops / (ms_per_step * 1e-3) / 1e12
     peak = PEAK_BF16_TFLOPS if lin.dtype == "bf16" else PEAK_F32_TFLOPS
 
+    step_median, step_min = time_each(torch, step, args.steps)
     # per-phase event timings (same launches, HIP events on the launch stream)
     ms_fwd = time_events(torch, fwd, args.steps)
     ms_bwd = time_events(torch, bwd, args.steps)
@@ -192,6 +273,7 @@ def main():
                                if lin.x_kind == "outlier" else f"{lin.name}: n={lin.n}, {lin.d_in}->{lin.d_out}, r={lin.r}, {lin.dtype}",
                    "with_dw": with_dw, "buffer_sets": len(sets)},
         "pct_of_bf16_mfma_peak": round(100.0 * value / peak, 2),
+        "ms_per_step_median": round(step_median, 4), "ms_per_step_min": round(step_min, 4),
         "ms_fwd": round(ms_fwd, 4), "ms_bwd": round(ms_bwd, 4),
         "factored_only": None if ms_bwd_nodw is None else {
             "ms_bwd": round(ms_bwd_nodw, 4),
