@@ -242,12 +242,22 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
   }
 }
 
-// Skinny product through the tuned kernel, the K range split over groups of work-groups so that about
-// `wgs_wanted` of them run: part[s][M][ldc] = A[:, K range s] . B[K range s, :], fp32.  Returns the number
+// K splits of a skinny product: as many as fill the chip's resident work-group slots exactly once (a
+// second, partly filled round would cost a whole extra pass of load latencies), each with at least
+// four K tiles.  lds_bytes: dynamic LDS of the kernel variant (4 waves per work-group).
+int64_t splitk_count(int64_t tiles, int64_t K, int lds_bytes) {
+  int64_t per_cu = (160 * 1024) / lds_bytes;
+  if (per_cu > 4) per_cu = 4;  // measured: five resident 64 x 64 work-groups per CU run slower than four
+  int64_t splits = (256 * per_cu) / tiles;
+  if (splits > K / 256) splits = K / 256;
+  return splits < 1 ? 1 : splits;
+}
+
+// Skinny product through the tuned kernel, the K range split over groups of work-groups (splitk_count): part[s][M][ldc] = A[:, K range s] . B[K range s, :], fp32.  Returns the number
 // of splits.  kb_rows: rows of an N-contiguous B that exist (K may be A's zero-padded length).
 template <int WM, int WN, int TM, int TN, bool KMAJ>
 int fast_gemm_splitk(const void* A, const void* B, float* part, int64_t M, int64_t N, int64_t K, int64_t lda,
-                     int64_t ldb, int64_t ldc, int64_t kb_rows, int wgs_wanted, Launcher& L) {
+                     int64_t ldb, int64_t ldc, int64_t kb_rows, Launcher& L) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   FastGemmParams p{};
   p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = part;
@@ -256,9 +266,7 @@ int fast_gemm_splitk(const void* A, const void* B, float* part, int64_t M, int64
   gemm_bf16_plan(p, BM, BN);  // tiles_m, tiles_n; the XCD super-tile order is not used with splits
   const int64_t tiles = ceil_div(M, BM) * ceil_div(N, BN);
   const unsigned tile_blocks = (unsigned)tiles;
-  int64_t splits = ceil_div(wgs_wanted, tiles);
-  if (splits > K / 256) splits = K / 256;  // at least four K tiles per work-group
-  if (splits < 1) splits = 1;
+  int64_t splits = splitk_count(tiles, K, gemm_bf16_lds_bytes<WM, WN, TM, TN>());
   p.k_per_split = round_up(ceil_div(K, splits), 64);
   splits = ceil_div(K, p.k_per_split);
   p.tile_blocks = (int)tile_blocks;
@@ -267,8 +275,6 @@ int fast_gemm_splitk(const void* A, const void* B, float* part, int64_t M, int64
                (size_t)gemm_bf16_lds_bytes<WM, WN, TM, TN>(), p);
   return (int)splits;
 }
-constexpr int kSkinnyWgs = 1024;        // work-groups a skinny split-K product aims for
-constexpr int kSkinnyMaxSplits = 64;    // bound used to size the partial buffers
 
 // Plan of the tuned sketch kernel for `channels` columns of a [n, ld] matrix.
 struct SketchPlan {
@@ -383,12 +389,8 @@ struct RsvdPlan {
   size_t off_omega, off_ut, off_yr_part, total;
 };
 
-// Upper bound of the splits fast_gemm_splitk picks.
-int64_t splitk_bound(int64_t tiles, int64_t K) {
-  int64_t splits = ceil_div(kSkinnyWgs, tiles);
-  if (splits > K / 256) splits = K / 256;
-  return splits < 1 ? 1 : splits;
-}
+// The number of splits fast_gemm_splitk picks (it sizes the partial buffers).
+int64_t splitk_bound(int64_t tiles, int64_t K, int lds_bytes) { return splitk_count(tiles, K, lds_bytes); }
 
 RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
   RsvdPlan pl{};
@@ -411,11 +413,11 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
     pl.off_rinv = take((size_t)k * k * 4);
   }
   if (pl.tuned) {
-    const int64_t fact_splits = splitk_bound(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad);
+    const int64_t fact_splits = splitk_bound(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad, gemm_bf16_lds_bytes<2, 2, 1, 2>());
     pl.off_fact_part = take((size_t)fact_splits * k * channels * 4);
     pl.off_ut = take((size_t)k * pl.n_pad * 2);
     if (!backward) {
-      const int64_t yr_splits = splitk_bound(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in);
+      const int64_t yr_splits = splitk_bound(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in, gemm_bf16_lds_bytes<2, 2, 1, 1>());
       pl.off_omega = take((size_t)2 * k * s.d_in * 2);
       pl.off_yr_part = take((size_t)yr_splits * s.n * 2 * k * 4);
     }
@@ -501,7 +503,7 @@ void rsvd_factor_tuned(const acc_linear_desc* d, const Shape& s, const RsvdPlan&
     L(transpose_pad_kernel<bf16>, dim3((unsigned)ceil_div(pl.n_pad * k, 256)), dim3(256), (const bf16*)U, s.n, (int)k,
       pl.n_pad, ut);
   const int splits = fast_gemm_splitk<2, 2, 1, 2, false>(ut, A, part, k, channels, pl.n_pad, pl.n_pad, lda, channels,
-                                                       s.n, kSkinnyWgs, L);
+                                                       s.n, L);
   const unsigned blocks = (unsigned)ceil_div(k * channels, 256);
   if (transposed) L(reduce_store_kernel<bf16, false>, dim3(blocks), dim3(256), (const float*)part, splits, k, channels, (bf16*)out);
   else L(reduce_store_kernel<bf16, true>, dim3(blocks), dim3(256), (const float*)part, splits, k, channels, (bf16*)out);
@@ -685,7 +687,7 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
     L(omega_hilo_kernel, dim3((unsigned)ceil_div(s.d_in / 4 * k, 256)), dim3(256), make_sketch_params(&od), s.d_in,
       (int)k, s.d_in, omega);
     const int splits = fast_gemm_splitk<2, 2, 1, 1, true>(X, omega, yr_part, s.n, 2 * k, s.d_in, s.ldx, s.d_in, 2 * k,
-                                                        0, kSkinnyWgs, L);
+                                                        0, L);
     L(combine_hilo_kernel, dim3((unsigned)ceil_div(s.n * k, 256)), dim3(256), (const float*)yr_part, splits, s.n, (int)k,
       y0);
   } else {
