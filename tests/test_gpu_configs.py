@@ -78,3 +78,11 @@ def test_c5_linears_sampled(acc, name):
     """8B-shaped layer, n = 65536 tokens, r = 512, low-rank-plus-noise activations."""
     lin = [l for l in inputs.config("c5") if l.name == name][0]
     _sampled_check(acc, lin, np.random.default_rng(3))
+
+
+def test_operands_beyond_two_gib_sampled(acc):
+    """X and dX of 2.3 GB each: byte offsets inside one operand exceed 2^31 (the kernels address with
+    per-tile 64-bit bases plus unsigned 32-bit offsets); ragged token count."""
+    lin = inputs.Linear("big_x", 140003, 8192, 1024, 128, x_kind="plain")
+    assert lin.n * lin.d_in * 2 > 2 ** 31
+    _sampled_check(acc, lin, np.random.default_rng(4))
