@@ -282,3 +282,11 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(acc):
         torch.cuda.synchronize()
         for k in outs:
             assert torch.equal(outs[k], eager[k]), (rep, k)
+
+
+@pytest.mark.parametrize("n,d_in,d_out,r", [(1000, 512, 640, 128), (777, 520, 264, 48), (2500, 576, 1096, 64)])
+def test_row_offsets_crossing_2_pow_34(acc, n, d_in, d_out, r):
+    """A shard whose global token indices cross 2^34: the high bits move into the fourth counter word
+    (tuned 8-wave and 4-wave sketch kernels and the generic one)."""
+    lin = inputs.Linear(f"hi_offset_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16", seed=0x5EED5EED5EED)
+    _check(acc, lin, row_offset=(1 << 34) - 512)
