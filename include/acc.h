@@ -124,7 +124,7 @@ int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, 
  * power iteration, no final rotation to singular vectors:
  *   Omega [d_in, r] Gaussian, Omega[c, j] = the Philox normal of (seed, token index := c, column j);
  *   Yr = X.Omega;  Yr = U.R, U^T.U = I, diag(R) > 0 (Cholesky QR, applied twice);  V = X^T.U.
- * Here desc->r is the rank: multiple of 8, 8 <= r <= 128, r <= n, r <= d_in (else ACC_ERR_SHAPE);
+ * Here desc->r is the rank: multiple of 8, 8 <= r <= 64, r <= n, r <= d_in (else ACC_ERR_SHAPE);
  * row_offset is ignored; ACC_FLAG_SKIP_SKETCH and ACC_FLAG_ONE_LAUNCH are refused.  If Yr has
  * dependent columns (rank(X) < r) the corresponding columns of U and V are zero; U.V^T is still the
  * projection of X onto the range of Yr.  U and V are stored as factor_dtype.                        */

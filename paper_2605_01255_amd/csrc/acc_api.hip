@@ -286,7 +286,7 @@ struct SketchPlan {
 
 SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, int64_t ld) {
   SketchPlan sp{};
-  sp.fast = d->io_dtype == ACC_BF16 && d->r % 64 == 0 && n * ld * 2 <= kMaxOperandBytes &&
+  sp.fast = d->io_dtype == ACC_BF16 && n * ld * 2 <= kMaxOperandBytes &&
             channels * d->r * 4 <= kMaxOperandBytes / 2;
   if (!sp.fast) {
     sp.G = generic_sketch_splits(n, channels, d->r);
@@ -294,7 +294,7 @@ SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, in
   }
   if (d->r % 128 == 0) { sp.ch = 512; sp.rc = 128; } else { sp.ch = 1024; sp.rc = 64; }
   sp.n_cslab = (int)ceil_div(channels, sp.ch);
-  sp.n_js = (int)(d->r / sp.rc);
+  sp.n_js = (int)ceil_div(d->r, sp.rc);  // the last column slice may be partly empty (rank % 64 != 0)
   int64_t G = (256 + sp.n_cslab * sp.n_js / 2) / (sp.n_cslab * sp.n_js);
   const int64_t max_by_tokens = ceil_div(n, 256);
   if (G > max_by_tokens) G = max_by_tokens;
@@ -459,9 +459,7 @@ void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, const float*
   L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, s.n, (int)k, rows, gram_part);
   L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, parts, k * k, gram);
   if (k <= 32) L(chol_inverse_small_kernel<32, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
-  else if (k <= 64) L(chol_inverse_small_kernel<64, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
-  else L.launch_lds(chol_inverse_kernel, dim3(1), dim3(256), (size_t)k * k * sizeof(double), (const float*)gram, 1, rinv,
-                    (int)k);
+  else L(chol_inverse_small_kernel<64, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
   const int64_t kp = round_up(k, 32);
   const size_t lds = (size_t)(64 * (kp + 1) + kp * (kp % 64 == 0 ? kp + 32 : kp)) * sizeof(float);
   const int64_t rows_out = Ut ? pl.n_pad : s.n;

@@ -1,4 +1,4 @@
-// Small dense kernel of the RSVD compressor (Experimental Setup: randomized SVD of Halko et al.): the
+// Small dense kernels of the RSVD compressor (Experimental Setup: randomized SVD of Halko et al.): the
 // triangular factor of a k x k Gram matrix and its inverse, the middle step of a Cholesky QR.  The large
 // products around it (X.Omega, Yr^T.Yr, Yr.R^-1, X^T.U, U^T.dY) run on the generic MFMA kernels.
 #pragma once
@@ -7,78 +7,16 @@
 
 namespace acc {
 
-constexpr int kRsvdMaxRank = 128;  // k x k doubles must fit the 160 KB of LDS
+constexpr int kRsvdMaxRank = 64;   // the k x k factorisation runs on one wave, one matrix row per lane
 
-// G = sum of `parts` matrices [k, k] (symmetric positive semi-definite, fp32) -> Rinv [k, k] fp32 with G = R^T R, R upper
-// triangular with positive diagonal, Rinv = R^-1 (upper triangular).  One work-group, fp64 inside.
+// G [k, k] (symmetric positive semi-definite, fp32) -> Rinv [k, k] fp32 with G = R^T R, R upper triangular
+// with positive diagonal, Rinv = R^-1 (upper triangular), for k <= K (K = 32 or 64), by ONE wave entirely in
+// registers: lane i holds row i of the symmetric matrix (padded to K with the identity), values move
+// between lanes by v_readlane broadcasts; no LDS, no barriers (the k sequential steps are pure latency, and
+// an LDS version with a barrier per step measured 2-4x slower).
 // A pivot that is not positive beyond rounding (column j of the factored matrix depends on the earlier
-// ones) is dropped: row and column j of Rinv are zero, so the corresponding basis vector comes out as
-// zero and the span of the others is unchanged.
-// Dynamic LDS: k * k doubles.
-__global__ __launch_bounds__(256) void chol_inverse_kernel(const float* __restrict__ G, int parts,
-                                                           float* __restrict__ Rinv, int k) {
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  double* A = (double*)smem_raw;  // [k][k]; the upper triangle becomes R
-  __shared__ double s_maxdiag;
-  __shared__ int s_dead[kRsvdMaxRank];
-  __shared__ double s_diag[kRsvdMaxRank];
-  const int tid = threadIdx.x, nt = blockDim.x;  // one wave for small k (barriers then cost nothing), four above
-  // G = sum of the `parts` partial Gram matrices, added in order (loads issued eight at a time)
-  for (int e = tid; e < k * k; e += nt) {
-    double sum = 0.0;
-    for (int g0 = 0; g0 < parts; g0 += 8) {
-      float v[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = g0 + t < parts ? G[(int64_t)(g0 + t) * k * k + e] : 0.f;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) sum += (double)v[t];
-    }
-    A[e] = sum;
-  }
-  __syncthreads();
-  if (tid == 0) {
-    double m = 0.0;
-    for (int j = 0; j < k; ++j) m = A[j * k + j] > m ? A[j * k + j] : m;
-    s_maxdiag = m;
-  }
-  __syncthreads();
-  const double tol = s_maxdiag * 1e-6;  // fp32 Gram: entries carry ~1e-7 relative rounding
-  for (int j = 0; j < k; ++j) {
-    const double piv = A[j * k + j];
-    const bool dead = !(piv > tol);
-    __syncthreads();  // everyone has read the pivot before row j is scaled
-    if (tid == 0) s_dead[j] = dead ? 1 : 0;
-    const double inv_d = dead ? 0.0 : 1.0 / sqrt(piv);
-    for (int c = j + tid; c < k; c += nt) A[j * k + c] = dead ? 0.0 : A[j * k + c] * inv_d;  // R[j][c]
-    __syncthreads();
-    const int m = k - j - 1;  // trailing (m x m) update, upper triangle only
-    for (int e = tid; e < m * m; e += nt) {
-      const int i = j + 1 + e / m, c = j + 1 + e % m;
-      if (c >= i) A[i * k + c] -= A[j * k + i] * A[j * k + c];
-    }
-    __syncthreads();
-  }
-  // Back substitution, one column c of the inverse per thread: R x = e_c, x[i] = 0 for i > c.  x[i], i < c,
-  // is kept in the unused lower triangle at A[c][i]; x[c] in s_diag[c].  Dropped pivots give x = 0.
-  for (int c = tid; c < k; c += nt) {
-    for (int i = c; i >= 0; --i) {
-      double sum = (i == c) ? 1.0 : 0.0;
-      for (int t = i + 1; t <= c; ++t) sum -= A[i * k + t] * (t == c ? s_diag[c] : A[c * k + t]);
-      const double xi = (s_dead[i] || s_dead[c]) ? 0.0 : sum / A[i * k + i];
-      if (i == c) s_diag[c] = xi; else A[c * k + i] = xi;
-    }
-  }
-  __syncthreads();
-  for (int e = tid; e < k * k; e += nt) {
-    const int i = e / k, c = e % k;
-    Rinv[e] = i < c ? (float)A[c * k + i] : (i == c ? (float)s_diag[c] : 0.f);
-  }
-}
-
-// The same factorisation and inverse for k <= K (K = 32 or 64) by ONE wave, entirely in registers: lane i
-// holds row i of the symmetric matrix (padded to K with the identity), values move between lanes by
-// v_readlane broadcasts; no LDS, no barriers.  About 4x faster than the LDS kernel at k = 32, where the
-// k sequential steps are pure latency.
+// ones) is dropped: row and column j of Rinv are zero, so the corresponding basis vector comes out as zero
+// and the span of the others is unchanged.
 __device__ __forceinline__ float lane_bcast(float v, int src_lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
 }

@@ -56,7 +56,10 @@ __device__ __forceinline__ void store_partial_tile(const f32x16 (&acc)[CWB], flo
                                         : (uint32_t)((rowi * C + mb * 32) * 4);
       const float v = acc[mb][e];
       // transposed: a channel past the end would land in the next row, so it is sent out of range
-      const uint32_t vo = (TRANSPOSED && cb0 + mb * 32 + lcol >= C) ? 0xFFFFFFF0u : voff;
+      // !transposed: a sketch column past r (rank not a multiple of the tile's columns) would land in the
+      // next channel's row; transposed, such rows fall behind the end of the buffer by themselves
+      const uint32_t vo = ((TRANSPOSED && cb0 + mb * 32 + lcol >= C) || (!TRANSPOSED && j0 + lcol >= r))
+                              ? 0xFFFFFFF0u : voff;
       __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, vo, soff, 0);
     }
   }

@@ -138,7 +138,7 @@ def test_rsvd_entry_points_validate_the_rank():
     args = (0x1000, 0x2000, 0x3000, 0x4000, 0x6000, 0x5000, 1 << 40, None)
     ok = dict(n=256, d_in=256, d_out=512)
     assert f(ctypes.byref(acc.make_desc(**ok, r=8)), *args) in (0, -6)
-    for bad_r in (4, 12, 136, 256):
+    for bad_r in (4, 12, 72, 128, 256):
         assert f(ctypes.byref(acc.make_desc(**ok, r=bad_r)), *args) == -2, bad_r
     assert f(ctypes.byref(acc.make_desc(n=16, d_in=256, d_out=512, r=32)), *args) == -2      # n < rank
     assert f(ctypes.byref(acc.make_desc(**ok, r=16, flags=acc.ACC_FLAG_SKIP_SKETCH)), *args) == -1
@@ -147,4 +147,4 @@ def test_rsvd_entry_points_validate_the_rank():
     assert need > 0 and acc.acc_rsvd_workspace_bytes(d, True) > 0
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, 0x4000, 0x6000, 0x5000, need - 1, None) == -5
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, None, 0x6000, 0x5000, need, None) == -1
-    assert acc.acc_rsvd_workspace_bytes(acc.make_desc(**ok, r=136), False) == 0
+    assert acc.acc_rsvd_workspace_bytes(acc.make_desc(**ok, r=72), False) == 0

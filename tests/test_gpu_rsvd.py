@@ -71,8 +71,8 @@ SHAPES = [
     (777, 520, 264, 32, "bf16"),
     (1000, 512, 640, 8, "bf16"),        # the paper's smallest rank
     (4100, 1024, 3080, 64, "bf16"),     # tuned GEMMs for the exact products and dW
-    (2049, 1032, 1544, 128, "bf16"),    # largest rank, ragged everything (generic kernels: d_in % 64 != 0)
-    (3001, 1024, 1544, 128, "bf16"),    # largest rank on the split-K path, ragged token count
+    (2049, 1032, 1544, 64, "bf16"),     # largest rank, ragged everything (generic kernels: d_in % 64 != 0)
+    (3001, 1024, 1544, 48, "bf16"),     # rank padded to 64 inside the kernels, split-K path, ragged token count
     (16384, 3072, 3072, 32, "bf16"),    # the 3B-shaped projection at the paper's rank
 ]
 
