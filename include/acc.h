@@ -46,7 +46,8 @@ typedef enum { ACC_F32 = 0, ACC_BF16 = 1 } acc_dtype;
 enum {
   ACC_OK = 0,
   ACC_ERR_INVALID_ARG = -1, /* NULL descriptor or required pointer, unknown flag            */
-  ACC_ERR_SHAPE = -2,       /* a size is <= 0, r % 16 != 0, d_in % 8 or d_out % 8 != 0,
+  ACC_ERR_SHAPE = -2,       /* a size is <= 0 or above its limit (n <= 2^30, d_in, d_out <= 2^21,
+                               r <= 2^16), r % 16 != 0, d_in % 8 or d_out % 8 != 0,
                                a row stride smaller than the row or not a multiple of 8,
                                row_offset % 4 != 0                                           */
   ACC_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                              */

@@ -35,7 +35,8 @@ int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16) {
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
   if (d->r % r_multiple || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;
-  if (d->n > (int64_t)1 << 40 || d->d_in > (1 << 21) || d->d_out > (1 << 21) || d->r > (1 << 16))
+  // limits that keep every grid dimension and 32-bit tile count in range
+  if (d->n > (int64_t)1 << 30 || d->d_in > (1 << 21) || d->d_out > (1 << 21) || d->r > (1 << 16))
     return ACC_ERR_SHAPE;
   if (d->row_offset % 4) return ACC_ERR_SHAPE;
   s->n = d->n; s->d_in = d->d_in; s->d_out = d->d_out; s->r = d->r;
