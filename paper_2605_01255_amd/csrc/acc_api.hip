@@ -254,8 +254,8 @@ int64_t splitk_count(int64_t tiles, int64_t K, int lds_bytes) {
   return splits < 1 ? 1 : splits;
 }
 
-// Skinny product through the tuned kernel, the K range split over groups of work-groups (splitk_count): part[s][M][ldc] = A[:, K range s] . B[K range s, :], fp32.  Returns the number
-// of splits.  kb_rows: rows of an N-contiguous B that exist (K may be A's zero-padded length).
+// Skinny product through the tuned kernel, the K range split over groups of work-groups (splitk_count):
+// part[s][M][ldc] = A[:, K range s] . B[K range s, :], fp32.  Returns the number of splits.  kb_rows: rows of an N-contiguous B that exist (K may be A's zero-padded length).
 template <int WM, int WN, int TM, int TN, bool KMAJ>
 int fast_gemm_splitk(const void* A, const void* B, float* part, int64_t M, int64_t N, int64_t K, int64_t lda,
                      int64_t ldb, int64_t ldc, int64_t kb_rows, Launcher& L) {
@@ -390,8 +390,6 @@ struct RsvdPlan {
   size_t off_omega, off_ut, off_yr_part, total;
 };
 
-// The number of splits fast_gemm_splitk picks (it sizes the partial buffers).
-int64_t splitk_bound(int64_t tiles, int64_t K, int lds_bytes) { return splitk_count(tiles, K, lds_bytes); }
 
 RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
   RsvdPlan pl{};
@@ -414,11 +412,11 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
     pl.off_rinv = take((size_t)k * k * 4);
   }
   if (pl.tuned) {
-    const int64_t fact_splits = splitk_bound(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad, gemm_bf16_lds_bytes<2, 2, 1, 2>());
+    const int64_t fact_splits = splitk_count(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad, gemm_bf16_lds_bytes<2, 2, 1, 2>());
     pl.off_fact_part = take((size_t)fact_splits * k * channels * 4);
     pl.off_ut = take((size_t)k * pl.n_pad * 2);
     if (!backward) {
-      const int64_t yr_splits = splitk_bound(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in, gemm_bf16_lds_bytes<2, 2, 1, 1>());
+      const int64_t yr_splits = splitk_count(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in, gemm_bf16_lds_bytes<2, 2, 1, 1>());
       pl.off_omega = take((size_t)2 * k * s.d_in * 2);
       pl.off_yr_part = take((size_t)yr_splits * s.n * 2 * k * 4);
     }
