@@ -24,7 +24,9 @@ def acc():
     return binding
 
 
-def run_rsvd(acc, lin, data, flags=0, factor_dtype=None, dw_dtype=None, want_dw=True, seed=None):
+def run_rsvd(acc, lin, data, flags=0, factor_dtype=None, dw_dtype=None, want_dw=True, seed=None, pad=(0, 0, 0),
+             dw_init=None):
+    """pad = extra elements per row of X/dX, W, Y/dY (strided operands); dw_init: starting value of dW."""
     import torch
     dev = "cuda:0"
     code = acc.ACC_BF16 if lin.dtype == "bf16" else acc.ACC_F32
@@ -32,22 +34,39 @@ def run_rsvd(acc, lin, data, flags=0, factor_dtype=None, dw_dtype=None, want_dw=
     dcode = code if dw_dtype is None else dw_dtype
     seed = lin.seed if seed is None else seed
     w_oi = bool(flags & acc.ACC_FLAG_W_OUT_IN)
-    X, dY = acc.to_device(data["X"], dev), acc.to_device(data["dY"], dev)
-    W = acc.to_device(np.ascontiguousarray(data["W"].T) if w_oi else data["W"], dev)
+    def padded(arr, extra):
+        t = acc.to_device(arr, dev)
+        if not extra:
+            return t
+        buf = torch.full((arr.shape[0], arr.shape[1] + extra), float("nan"), dtype=t.dtype, device=dev)
+        buf[:, :arr.shape[1]] = t
+        return buf
+
+    w_host = np.ascontiguousarray(data["W"].T) if w_oi else data["W"]
+    X, dY, W = padded(data["X"], pad[0]), padded(data["dY"], pad[2]), padded(w_host, pad[1])
     desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=seed, io_dtype=code, factor_dtype=fcode,
-                         dw_dtype=dcode, flags=flags)
+                         dw_dtype=dcode, flags=flags, ldx=X.shape[1] if pad[0] else 0,
+                         ldw=W.shape[1] if pad[1] else 0, ldy=dY.shape[1] if pad[2] else 0)
     tdt, fdt, ddt = acc.torch_dtype(code), acc.torch_dtype(fcode), acc.torch_dtype(dcode)
-    Y = torch.full((lin.n, lin.d_out), 7.0, dtype=tdt, device=dev)
-    dX = torch.full((lin.n, lin.d_in), 7.0, dtype=tdt, device=dev)
+    Y = torch.full((lin.n, lin.d_out + pad[2]), 7.0, dtype=tdt, device=dev)
+    dX = torch.full((lin.n, lin.d_in + pad[0]), 7.0, dtype=tdt, device=dev)
     U = torch.full((lin.n, lin.r), 7.0, dtype=fdt, device=dev)
     V = torch.full((lin.d_in, lin.r), 7.0, dtype=fdt, device=dev)
     Gr = torch.full((lin.d_out, lin.r) if w_oi else (lin.r, lin.d_out), 7.0, dtype=fdt, device=dev)
     dW = torch.full((lin.d_out, lin.d_in) if w_oi else (lin.d_in, lin.d_out), 7.0, dtype=ddt, device=dev) \
         if want_dw else None
+    if dw_init is not None:
+        dW.copy_(torch.from_numpy(dw_init).to(dev).to(ddt))
     acc.acc_linear_fwd_rsvd(desc, X, W, Y, U, V, acc.alloc_workspace(desc, False, dev, rsvd=True))
     acc.acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, dW, acc.alloc_workspace(desc, True, dev, rsvd=True))
     torch.cuda.synchronize()
     out = {k: acc.to_host_f64(v) for k, v in (("Y", Y), ("dX", dX), ("U", U), ("V", V), ("Gr", Gr))}
+    if pad[2]:
+        assert np.all(out["Y"][:, lin.d_out:] == 7.0)
+        out["Y"] = out["Y"][:, :lin.d_out]
+    if pad[0]:
+        assert np.all(out["dX"][:, lin.d_in:] == 7.0)
+        out["dX"] = out["dX"][:, :lin.d_in]
     if want_dw:
         out["dW"] = acc.to_host_f64(dW)
     return out
@@ -133,3 +152,18 @@ def test_rsvd_is_deterministic_and_seed_dependent(acc):
     c = run_rsvd(acc, lin, data, seed=6)
     assert np.array_equal(a["Y"], c["Y"]) and np.array_equal(a["dX"], c["dX"])   # exact products ignore the seed
     assert not np.array_equal(a["U"], c["U"])
+
+
+@pytest.mark.parametrize("n,d_in,d_out,k", [(1500, 512, 768, 32), (515, 264, 136, 16)])
+def test_rsvd_strided_operands_and_accumulated_gradient(acc, n, d_in, d_out, k):
+    """Row strides larger than the rows on every strided operand (split-K and generic kernels), and
+    ACC_FLAG_DW_ACCUMULATE adding the RSVD gradient onto an existing float dW."""
+    lin = inputs.Linear(f"rsvd_strided_{n}", n, d_in, d_out, k, dtype="bf16", seed=4)
+    data = inputs.make(lin)
+    rng = np.random.default_rng(0)
+    start = rng.standard_normal((d_in, d_out)).astype(np.float32) * 1e-3
+    got = run_rsvd(acc, lin, data, pad=(64, 8, 72), dw_dtype=0, flags=acc.ACC_FLAG_DW_ACCUMULATE, dw_init=start)
+    want, _ = oracle_rsvd(lin, data)
+    for key in ("Y", "dX", "U", "V", "Gr"):
+        assert gu.rel(got[key], want[key]) <= 1e-2, key
+    assert gu.rel(got["dW"], start.astype(np.float64) + want["dW"]) <= 1e-2

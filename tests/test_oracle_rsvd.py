@@ -127,3 +127,23 @@ def test_paper_orientation_of_rsvd_gradient_factors():
     assert np.allclose(Gr2, Gr.T) and np.allclose(dW2, dW.T)
     # Sec. 4 written out: G^_W = ((grad_Z L)^T U) V^T
     assert np.allclose(dW2, (dY.T @ U) @ V.T)
+
+
+def test_backward_factors_against_integer_loops():
+    """Gr = U^T dY and dW = V Gr with explicit integer factors, element by element (Sec. 4)."""
+    rng = np.random.default_rng(6)
+    n, d, d_out, k = 6, 5, 4, 3
+    U = rng.integers(-3, 4, size=(n, k)); V = rng.integers(-3, 4, size=(d, k))
+    dY = rng.integers(-3, 4, size=(n, d_out)); W = rng.integers(-3, 4, size=(d, d_out))
+    dX, Gr, dW = orc.linear_bwd_rsvd(dY, W, U, V)
+    for j in range(k):
+        for o in range(d_out):
+            assert Gr[j, o] == sum(int(U[i, j]) * int(dY[i, o]) for i in range(n))
+    for c in range(d):
+        for o in range(d_out):
+            assert dW[c, o] == sum(int(V[c, j]) * sum(int(U[i, j]) * int(dY[i, o]) for i in range(n)) for j in range(k))
+            # = row c of X^ = U V^T against dY
+            assert dW[c, o] == sum(sum(int(U[i, j]) * int(V[c, j]) for j in range(k)) * int(dY[i, o]) for i in range(n))
+    for i in range(n):
+        for c in range(d):
+            assert dX[i, c] == sum(int(dY[i, o]) * int(W[c, o]) for o in range(d_out))
