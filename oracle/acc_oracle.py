@@ -165,7 +165,7 @@ def linear_bwd(dY, W, Xs, seed: int = 0, r: int = 0, row_offset: int = 0, S=None
 # The paper gives no parameters beyond the rank; the reading used here is the basic randomized range
 # finder followed by the projection onto it, with no oversampling, no power iteration and no final
 # rotation to singular vectors (a rotation inside the k-dimensional subspace changes neither X^ nor
-# the gradient estimate):
+# the gradient estimate); optional rounds of subspace iteration sharpen the range (rsvd_factors):
 #   Omega [d_in, k] Gaussian (same Philox map as S, the channel index in place of the token index),
 #   Yr = X Omega,  Yr = U R with U^T U = I and diag(R) > 0 (thin QR, unique for full column rank),
 #   V = X^T U,     X^ = U V^T = U U^T X,
@@ -185,22 +185,31 @@ def orthonormal_basis(Yr):
     return Q * sign[None, :], R * sign[:, None]
 
 
-def rsvd_factors(X, seed: int, k: int, Omega=None):
-    """U [n, k], V [d_in, k] of the RSVD-compressed activation X^ = U V^T."""
+def rsvd_factors(X, seed: int, k: int, Omega=None, power_iters: int = 0):
+    """U [n, k], V [d_in, k] of the RSVD-compressed activation X^ = U V^T.
+
+    power_iters = q > 0 adds q rounds of subspace iteration (Halko et al., randomized subspace
+    iteration: the basis is re-orthonormalised after every product, which is what keeps the small
+    singular directions from being lost to rounding):  Z = orth(X^T U),  U = orth(X Z).
+    The range approaches the dominant k-dimensional left singular subspace of X as q grows.
+    """
     X = np.asarray(X, dtype=np.float64)
     if Omega is None:
         Omega = range_finder_matrix(seed, X.shape[1], k)
     U, _ = orthonormal_basis(np.matmul(X, Omega))
+    for _ in range(power_iters):
+        Z, _ = orthonormal_basis(np.matmul(X.T, U))
+        U, _ = orthonormal_basis(np.matmul(X, Z))
     V = np.matmul(X.T, U)
     return U, V
 
 
-def linear_fwd_rsvd(X, W, seed: int = 0, k: int = 0, Omega=None, w_out_in: bool = False):
+def linear_fwd_rsvd(X, W, seed: int = 0, k: int = 0, Omega=None, w_out_in: bool = False, power_iters: int = 0):
     """Y = X W (exact) and the stored factors U, V of the RSVD-compressed input."""
     X = np.asarray(X, dtype=np.float64)
     W = np.asarray(W, dtype=np.float64)
     Y = np.matmul(X, W.T) if w_out_in else np.matmul(X, W)
-    U, V = rsvd_factors(X, seed, k, Omega)
+    U, V = rsvd_factors(X, seed, k, Omega, power_iters)
     return Y, U, V
 
 

@@ -147,3 +147,35 @@ def test_backward_factors_against_integer_loops():
     for i in range(n):
         for c in range(d):
             assert dX[i, c] == sum(int(dY[i, o]) * int(W[c, o]) for o in range(d_out))
+
+
+def test_subspace_iteration_approaches_the_best_rank_k_approximation():
+    """With q rounds of subspace iteration the projection error falls towards the Eckart-Young optimum
+    (it can never go below it), fast when the spectrum decays; q = 0 is the plain range finder; every
+    iterate is still an orthogonal projection of X; a matrix of rank <= k is reproduced for every q."""
+    rng = np.random.default_rng(8)
+    n, d, k = 300, 80, 10
+    Uo, _ = np.linalg.qr(rng.standard_normal((n, d)))
+    Vo, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    sig = 5.0 * 0.85 ** np.arange(d)
+    X = (Uo * sig) @ Vo.T
+    best = np.sqrt(np.sum(sig[k:] ** 2))
+    errs = []
+    for q in range(4):
+        U, V = orc.rsvd_factors(X, seed=2, k=k, power_iters=q)
+        assert np.allclose(U.T @ U, np.eye(k), atol=1e-12)
+        assert np.allclose(U.T @ (X - U @ V.T), 0, atol=1e-10)
+        errs.append(np.linalg.norm(X - U @ V.T))
+    U0, V0 = orc.rsvd_factors(X, seed=2, k=k)
+    assert errs[0] == np.linalg.norm(X - U0 @ V0.T)
+    assert all(e >= best * (1 - 1e-12) for e in errs)
+    assert errs[3] < errs[2] < errs[1] < errs[0]
+    assert errs[0] > 1.5 * best and errs[1] < 1.3 * best and errs[3] < 1.1 * best   # 2.11, 1.21, 1.09, 1.06 x optimum
+    # the dominant left singular subspace is what the iteration converges to
+    Uk = Uo[:, :k]
+    U5, _ = orc.rsvd_factors(X, seed=2, k=k, power_iters=12)
+    assert np.linalg.norm(Uk @ Uk.T - U5 @ U5.T) < 0.1 * np.linalg.norm(Uk @ Uk.T - U0 @ U0.T)
+    Xl = rng.standard_normal((n, 6)) @ rng.standard_normal((6, d))
+    for q in (0, 1, 3):
+        U, V = orc.rsvd_factors(Xl, seed=1, k=k, power_iters=q)
+        assert np.allclose(U @ V.T, Xl, atol=1e-9)
