@@ -328,8 +328,19 @@ def main():
     n_rs = max(5, args.steps // 4)
     ms_rf = time_events(torch, fwd_rsvd, n_rs)
     ms_rb = time_events(torch, bwd_rsvd, n_rs)
+    # the same forward with two rounds of subspace iteration (four more passes over X)
+    desc_rs2 = acc.make_desc(lin.n, lin.d_in, lin.d_out, k_rsvd, seed=lin.seed, io_dtype=code,
+                             flags=2 << acc.ACC_FLAG_RSVD_POWER_SHIFT)
+    ws_rf2 = acc.alloc_workspace(desc_rs2, False, dev, rsvd=True)
+
+    def fwd_rsvd2(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd_rsvd(desc_rs2, b.X, b.W, b.Y, U_rs, V_rs, ws_rf2)
+
+    fwd_rsvd2(0)
+    ms_rf2 = time_events(torch, fwd_rsvd2, n_rs)
     out["widened"] = {
-        "rsvd_rank32": {"ms_fwd": round(ms_rf, 4), "ms_bwd": round(ms_rb, 4),
+        "rsvd_rank32": {"ms_fwd": round(ms_rf, 4), "ms_bwd": round(ms_rb, 4), "ms_fwd_2_subspace_iterations": round(ms_rf2, 4),
                         "kept_bytes_per_token": round((lin.n + lin.d_in) * k_rsvd * 2 / lin.n, 2)},
         "bias_grad": {"ms": round(ms_db, 4), "bound": "hbm", "achieved": round(db_bytes / (ms_db * 1e-3) / 1e9, 1),
                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(db_bytes / (ms_db * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},

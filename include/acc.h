@@ -67,11 +67,17 @@ enum {
   ACC_FLAG_W_OUT_IN = 4u,    /* W is [d_out, ldw >= d_in] (the layout of torch.nn.Linear.weight
                                 and of the paper's Def. 3.1); Gr is then [d_out, r] and dW
                                 [d_out, d_in].  ACC_FLAG_ONE_LAUNCH is ignored with it.          */
+  ACC_FLAG_RSVD_POWER_1 = 1u << 8, /* acc_linear_fwd_rsvd only: one round of subspace iteration after the  */
+  ACC_FLAG_RSVD_POWER_2 = 2u << 8, /* range finder (two, three): Z = orth(X^T.U), U = orth(X.Z); refused   */
+  ACC_FLAG_RSVD_POWER_3 = 3u << 8, /* by the random-projection calls, ignored by acc_linear_bwd_rsvd.  Each
+                                      round costs two more passes over X.                                  */
   ACC_FLAG_DW_ACCUMULATE = 8u /* backward only, with dW != NULL: dW += Xs.Gr, not dW = Xs.Gr
                                 (gradient accumulation over micro-batches on the dense gradient,
                                 Sec. 4 update strategy (i)).  A float dW is rounded once per call;
                                 a bfloat16 dW rounds the product and then the sum.               */
 };
+
+#define ACC_FLAG_RSVD_POWER_SHIFT 8 /* flags bits 8..9: rounds of subspace iteration, 0..3 */
 
 typedef struct acc_linear_desc {
   int64_t n;            /* tokens (batch x sequence)                                         */
@@ -122,7 +128,7 @@ int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, 
 /* ---- RSVD compressor (Experimental Setup: randomized SVD of Halko, Martinsson and Tropp; Sec. 4: the
  * compressed activation is kept as two factors, X^ = U.V^T, U [n, r], V [d_in, r]) -------------------
  * Reading (the paper fixes only the rank): randomized range finder and projection, no oversampling, no
- * power iteration, no final rotation to singular vectors:
+ * final rotation to singular vectors, subspace iterations only on request (ACC_FLAG_RSVD_POWER_*):
  *   Omega [d_in, r] Gaussian, Omega[c, j] = the Philox normal of (seed, token index := c, column j);
  *   Yr = X.Omega;  Yr = U.R, U^T.U = I, diag(R) > 0 (Cholesky QR, applied twice);  V = X^T.U.
  * Here desc->r is the rank: multiple of 8, 8 <= r <= 64, r <= n, r <= d_in (else ACC_ERR_SHAPE);

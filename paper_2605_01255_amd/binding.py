@@ -17,6 +17,7 @@ ACC_FLAG_SKIP_SKETCH = 1
 ACC_FLAG_ONE_LAUNCH = 2
 ACC_FLAG_W_OUT_IN = 4
 ACC_FLAG_DW_ACCUMULATE = 8
+ACC_FLAG_RSVD_POWER_SHIFT = 8   # flags bits 8..9: rounds of subspace iteration of the RSVD forward
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
            "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_philox_dump_u32",

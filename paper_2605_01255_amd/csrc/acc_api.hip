@@ -28,9 +28,11 @@ struct Shape {
   int64_t n, d_in, d_out, r, ldx, ldw, ldy;
 };
 
-int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16) {
+int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16, uint32_t extra_flags = 0) {
   if (!d) return ACC_ERR_INVALID_ARG;
-  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
+  if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN | ACC_FLAG_DW_ACCUMULATE |
+                             extra_flags))
+    return ACC_ERR_INVALID_ARG;
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
@@ -388,8 +390,12 @@ struct RsvdPlan {
   int g_fact;   // token splits of V = X^T.U (forward) or Gr = U^T.dY (backward), generic path
   int64_t n_pad;  // tokens rounded up to 64 (K padding of the products over tokens)
   size_t off_y0, off_q1, off_gram_part, off_gram, off_rinv, off_fact_part;  // byte offsets
-  size_t off_omega, off_ut, off_yr_part, total;
+  size_t off_omega, off_ut, off_yr_part, off_z0, off_z1, off_zt_part, total;
 };
+
+// Rounds of subspace iteration asked for in the descriptor (RSVD entry points only).
+int rsvd_power_iters(const acc_linear_desc* d) { return (int)((d->flags >> ACC_FLAG_RSVD_POWER_SHIFT) & 3u); }
+
 
 
 RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
@@ -400,8 +406,7 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
   pl.n_pad = round_up(s.n, 64);
   pl.tuned = d->io_dtype == ACC_BF16 && d->factor_dtype == ACC_BF16 && s.d_in % 64 == 0 && s.n >= 256 &&
              s.n * ld_in * 2 <= kMaxOperandBytes && pl.n_pad * 2 * k * 4 <= kMaxOperandBytes;
-  pl.g_gram = (int)ceil_div(s.n, 64);   // one 64-row chunk per work-group where possible: a single load latency
-  if (pl.g_gram > 256) pl.g_gram = 256;
+  pl.g_gram = 256;  // at most this many slabs per Gram product (one 64-row chunk per work-group where possible)
   pl.g_fact = generic_sketch_splits(s.n, channels, k);
   size_t off = 0;
   auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
@@ -411,11 +416,19 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
     pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
     pl.off_gram = take((size_t)k * k * 4);
     pl.off_rinv = take((size_t)k * k * 4);
+    if (rsvd_power_iters(d)) {  // Z = X^T.U and its orthonormalised form, [d_in, k] fp32
+      pl.off_z0 = take((size_t)s.d_in * k * 4);
+      pl.off_z1 = take((size_t)s.d_in * k * 4);
+    }
   }
   if (pl.tuned) {
     const int64_t fact_splits = splitk_count(ceil_div(k, 64) * ceil_div(channels, 128), pl.n_pad, gemm_bf16_lds_bytes<2, 2, 1, 2>());
     pl.off_fact_part = take((size_t)fact_splits * k * channels * 4);
-    pl.off_ut = take((size_t)k * pl.n_pad * 2);
+    pl.off_ut = take((size_t)2 * k * pl.n_pad * 2);  // U^T, or [U_hi; U_lo]^T during subspace iterations
+    if (!backward && rsvd_power_iters(d)) {
+      const int64_t zt_splits = splitk_count(ceil_div(2 * k, 64) * ceil_div(s.d_in, 128), pl.n_pad, gemm_bf16_lds_bytes<2, 2, 1, 2>());
+      pl.off_zt_part = take((size_t)zt_splits * 2 * k * s.d_in * 4);
+    }
     if (!backward) {
       const int64_t yr_splits = splitk_count(ceil_div(s.n, 64) * ceil_div(2 * k, 64), s.d_in, gemm_bf16_lds_bytes<2, 2, 1, 1>());
       pl.off_omega = take((size_t)2 * k * s.d_in * 2);
@@ -446,30 +459,31 @@ void reduce_to(int out_dt, const float* part, int G, int64_t count, void* out, L
   else L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out);
 }
 
-// One Cholesky-QR pass: Q = Yin . R^-1 with Yin^T.Yin = R^T.R.  Q goes to any of: Qf (fp32 [n, k]),
-// Qt (factor dtype [n, k]), Ut (bf16 [k, n_pad], zero-padded transpose).
-void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, const float* Yin, float* Qf, void* Qt, int qt_dt,
-                      bf16* Ut, Launcher& L) {
+// One Cholesky-QR pass on a tall matrix Yin [m, k] fp32: Q = Yin . R^-1 with Yin^T.Yin = R^T.R.  Q goes to any
+// of: Qf (fp32 [m, k]), Qt (factor dtype [m, k]), Ut (bf16 [k, ldt] zero-padded transpose up to column
+// m_pad; [2k, ldt] hi / lo parts with `hilo`).
+void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, int64_t m, int64_t m_pad, const float* Yin,
+                      float* Qf, void* Qt, int qt_dt, bf16* Ut, int64_t ldt, bool hilo, Launcher& L) {
   const int64_t k = s.r;
   float* gram_part = (float*)(ws + pl.off_gram_part);
   float* rinv = (float*)(ws + pl.off_rinv);
   float* gram = (float*)(ws + pl.off_gram);
-  const int rows = (int)round_up(ceil_div(s.n, pl.g_gram), 64);
-  const int parts = (int)ceil_div(s.n, rows);
-  L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, s.n, (int)k, rows, gram_part);
+  const int rows = (int)round_up(ceil_div(m, pl.g_gram), 64);
+  const int parts = (int)ceil_div(m, rows);
+  L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, m, (int)k, rows, gram_part);
   L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, parts, k * k, gram);
   if (k <= 32) L(chol_inverse_small_kernel<32, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
   else L(chol_inverse_small_kernel<64, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
   const int64_t kp = round_up(k, 32);
   const size_t lds = (size_t)(64 * (kp + 1) + kp * (kp % 64 == 0 ? kp + 32 : kp)) * sizeof(float);
-  const int64_t rows_out = Ut ? pl.n_pad : s.n;
+  const int64_t rows_out = Ut ? m_pad : m;
   const dim3 grid((unsigned)ceil_div(rows_out, 64));
   if (qt_dt == ACC_BF16)
-    L.launch_lds(tall_times_small_kernel<bf16>, grid, dim3(256), lds, Yin, s.n, (int)k, (const float*)rinv, Qf, (bf16*)Qt,
-                 Ut, pl.n_pad, rows_out);
+    L.launch_lds(tall_times_small_kernel<bf16>, grid, dim3(256), lds, Yin, m, (int)k, (const float*)rinv, Qf, (bf16*)Qt,
+                 Ut, ldt, rows_out, hilo ? 1 : 0);
   else
-    L.launch_lds(tall_times_small_kernel<float>, grid, dim3(256), lds, Yin, s.n, (int)k, (const float*)rinv, Qf,
-                 (float*)Qt, Ut, pl.n_pad, rows_out);
+    L.launch_lds(tall_times_small_kernel<float>, grid, dim3(256), lds, Yin, m, (int)k, (const float*)rinv, Qf,
+                 (float*)Qt, Ut, ldt, rows_out, hilo ? 1 : 0);
 }
 
 // out[channels, k] (or its transpose) = A^T . U over the token axis, A [n, lda]; splits reduced by K4.
@@ -565,7 +579,7 @@ void dense_dw(const acc_linear_desc* desc, const Shape& s, const void* Xs, const
 }
 
 int validate_rsvd(const acc_linear_desc* d, Shape* s) {
-  const int rc = validate_desc(d, s, 8);
+  const int rc = validate_desc(d, s, 8, 3u << ACC_FLAG_RSVD_POWER_SHIFT);
   if (rc != ACC_OK) return rc;
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
   if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
@@ -675,19 +689,26 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
   float* q1 = (float*)(ws + pl.off_q1);
   const int64_t k = s.r;
 
-  // Yr = X . Omega, Omega[c, j] from the Philox map with the channel index in the token's place
-  acc_linear_desc od = *desc;
-  od.row_offset = 0;
-  if (pl.tuned) {
-    // Omega as hi + lo bfloat16 parts, one split-K pass of the tuned kernel over X, halves and splits folded
-    bf16* omega = (bf16*)(ws + pl.off_omega);
+  const int power_iters = rsvd_power_iters(desc);
+  bf16* omega = (bf16*)(ws + pl.off_omega);  // tuned path: [2k, d_in] hi / lo parts of the right factor of Yr
+  bf16* ut = (bf16*)(ws + pl.off_ut);        // tuned path: U^T ([U_hi; U_lo]^T while iterating), zero-padded
+  // y0 = X . B, B given as hi + lo bfloat16 parts [2k, d_in]: one split-K pass of the tuned kernel over X,
+  // halves and splits folded
+  auto times_hilo = [&]() {
     float* yr_part = (float*)(ws + pl.off_yr_part);
-    L(omega_hilo_kernel, dim3((unsigned)ceil_div(s.d_in / 4 * k, 256)), dim3(256), make_sketch_params(&od), s.d_in,
-      (int)k, s.d_in, omega);
     const int splits = fast_gemm_splitk<2, 2, 1, 1, true>(X, omega, yr_part, s.n, 2 * k, s.d_in, s.ldx, s.d_in, 2 * k,
                                                         0, L);
     L(combine_hilo_kernel, dim3((unsigned)ceil_div(s.n * k, 256)), dim3(256), (const float*)yr_part, splits, s.n, (int)k,
       y0);
+  };
+
+  // Yr = X . Omega, Omega[c, j] from the Philox map with the channel index in the token's place
+  acc_linear_desc od = *desc;
+  od.row_offset = 0;
+  if (pl.tuned) {
+    L(omega_hilo_kernel, dim3((unsigned)ceil_div(s.d_in / 4 * k, 256)), dim3(256), make_sketch_params(&od), s.d_in,
+      (int)k, s.d_in, omega);
+    times_hilo();
   } else {
     GemmParams p{};
     p.A = X; p.B = nullptr; p.C = y0;
@@ -698,9 +719,52 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
     if (desc->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, 1, L);
     else launch_generic<float, float, float, float, true, true>(p, 1, L);
   }
-  // Two Cholesky-QR passes: the second removes the loss of orthogonality of the first.
-  cholesky_qr_pass(s, pl, ws, y0, q1, nullptr, ACC_F32, nullptr, L);
-  cholesky_qr_pass(s, pl, ws, q1, nullptr, U, desc->factor_dtype, pl.tuned ? (bf16*)(ws + pl.off_ut) : nullptr, L);
+  // Orthonormalise with two Cholesky-QR passes (the second removes the loss of orthogonality of the
+  // first), then `power_iters` rounds of subspace iteration: Z = orth(X^T.U), U = orth(X.Z).
+  for (int it = 0; it <= power_iters; ++it) {
+    const bool last = it == power_iters;
+    cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, y0, q1, nullptr, ACC_F32, nullptr, 0, false, L);
+    if (last) {
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, nullptr, U, desc->factor_dtype, pl.tuned ? ut : nullptr, pl.n_pad,
+                       false, L);
+      break;
+    }
+    float* z0 = (float*)(ws + pl.off_z0);
+    float* z1 = (float*)(ws + pl.off_z1);
+    if (pl.tuned) {
+      // U as hi + lo parts, transposed; Z^T = [U_hi; U_lo] . X over the tokens with the K range split
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, nullptr, nullptr, ACC_F32, ut, pl.n_pad, true, L);
+      float* zt_part = (float*)(ws + pl.off_zt_part);
+      const int splits = fast_gemm_splitk<2, 2, 1, 2, false>(ut, X, zt_part, 2 * k, s.d_in, pl.n_pad, pl.n_pad, s.ldx,
+                                                           s.d_in, s.n, L);
+      L(combine_hilo_t_kernel, dim3((unsigned)ceil_div(k * s.d_in, 256)), dim3(256), (const float*)zt_part, splits,
+        s.d_in, (int)k, z0);
+      // orth(Z), the second pass writing it as hi + lo parts [2k, d_in]: the right factor of the next X . Z
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, z1, nullptr, ACC_F32, nullptr, 0, false, L);
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z1, nullptr, nullptr, ACC_F32, omega, s.d_in, true, L);
+      times_hilo();
+    } else {
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, y0, nullptr, ACC_F32, nullptr, 0, false, L);  // U fp32 -> y0
+      float* part = (float*)(ws + pl.off_fact_part);
+      GemmParams g{};  // Z [d_in, k] = X^T . U, token range split
+      g.A = X; g.B = y0; g.C = part;
+      g.M = s.d_in; g.N = k; g.K = s.n;
+      g.a_sm = 1; g.a_sk = s.ldx; g.b_sk = k; g.b_sn = 1; g.c_sm = k; g.c_sn = 1;
+      g.k_per_split = round_up(ceil_div(s.n, pl.g_fact), 32);
+      g.c_split_stride = s.d_in * k;
+      const int splits = (int)ceil_div(s.n, g.k_per_split);
+      rsvd_gemm(desc->io_dtype, ACC_F32, ACC_F32, g, splits, L);
+      reduce_to(ACC_F32, part, splits, s.d_in * k, z0, L);
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, z1, nullptr, ACC_F32, nullptr, 0, false, L);
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z1, z0, nullptr, ACC_F32, nullptr, 0, false, L);  // orth(Z) -> z0
+      GemmParams y{};  // y0 [n, k] = X . Z
+      y.A = X; y.B = z0; y.C = y0;
+      y.M = s.n; y.N = k; y.K = s.d_in;
+      y.a_sm = s.ldx; y.a_sk = 1; y.b_sk = k; y.b_sn = 1; y.c_sm = k; y.c_sn = 1;
+      y.k_per_split = round_up(s.d_in, 32);
+      rsvd_gemm(desc->io_dtype, ACC_F32, ACC_F32, y, 1, L);
+    }
+  }
   // V = X^T . U with U as stored (rounded to the factor type), so that U V^T is the projection the
   // backward pass will use
   if (pl.tuned) rsvd_factor_tuned(desc, s, pl, ws, X, s.ldx, s.d_in, nullptr, false, V, L);

@@ -177,13 +177,15 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
 // Q = Y . Rinv for a tall Y [n, k] fp32 and a k x k fp32 Rinv, fp32 matrix instructions.  One work-group
 // per 64 rows, rows up to n_rows_out (>= n; rows past n count as zero).  Outputs, each optional:
 //   Qf  [n, k] fp32;  Qt [n, k] in TU (the stored factor);  Ut [k, ldt] bf16, the transpose with its
-//   columns n .. n_rows_out - 1 written as zero (K padding of the later products over tokens).
+//   columns n .. n_rows_out - 1 written as zero (K padding of the later products over tokens); with
+//   `hilo` Ut is [2k, ldt]: rows 0 .. k-1 the bf16 rounding of Q^T, rows k .. 2k-1 the bf16 rounding of
+//   the remainder, so that hi + lo carries Q to about 2^-17 relative through a bf16 matrix product.
 template <typename TU>
 __global__ __launch_bounds__(256) void tall_times_small_kernel(const float* __restrict__ Y, int64_t n, int k,
                                                                const float* __restrict__ Rinv,
                                                                float* __restrict__ Qf, TU* __restrict__ Qt,
                                                                bf16* __restrict__ Ut, int64_t ldt,
-                                                               int64_t n_rows_out) {
+                                                               int64_t n_rows_out, int hilo) {
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kp = (k + 31) / 32 * 32, nb = kp / 32;
@@ -220,7 +222,11 @@ __global__ __launch_bounds__(256) void tall_times_small_kernel(const float* __re
           if (Qf) Qf[row * k + col] = acc[e];
           if (Qt) Qt[row * k + col] = from_f32<TU>(acc[e]);
         }
-        if (Ut && row < n_rows_out) Ut[(int64_t)col * ldt + row] = row < n ? (bf16)acc[e] : (bf16)0.f;
+        if (Ut && row < n_rows_out) {
+          const bf16 hi = row < n ? (bf16)acc[e] : (bf16)0.f;
+          Ut[(int64_t)col * ldt + row] = hi;
+          if (hilo) Ut[(int64_t)(k + col) * ldt + row] = row < n ? (bf16)(acc[e] - (float)hi) : (bf16)0.f;
+        }
       }
     }
   }
@@ -266,6 +272,22 @@ __global__ __launch_bounds__(256) void combine_hilo_kernel(const float* __restri
     sum += row[j] + row[k + j];
   }
   Yr[idx] = sum;
+}
+
+// Z [cols, k] = transpose of the sum over splits of (part[s][j][c] + part[s][k + j][c]), part[s] being
+// [2k, cols] fp32: folds the K splits and the hi / lo halves of [Q_hi; Q_lo]^T-type products in a fixed
+// order.  One thread per input column pair (c, j), coalesced reads.
+__global__ __launch_bounds__(256) void combine_hilo_t_kernel(const float* __restrict__ part, int splits, int64_t cols,
+                                                             int k, float* __restrict__ Z) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // = j * cols + c
+  if (idx >= (int64_t)k * cols) return;
+  const int64_t j = idx / cols, c = idx - j * cols;
+  float sum = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float* p = part + (int64_t)s * 2 * k * cols;
+    sum += p[j * cols + c] + p[(k + j) * cols + c];
+  }
+  Z[c * k + j] = sum;
 }
 
 // Ut [k, ld] = U^T with the columns n .. ld - 1 zeroed (ld = n rounded up to 64: the K padding of the

@@ -67,6 +67,7 @@ def test_invalid_descriptors_are_refused():
     assert _fwd(acc.make_desc(**ok, io_dtype=7)) == -4
     assert _fwd(acc.make_desc(**ok, factor_dtype=-1)) == -4
     assert _fwd(acc.make_desc(**ok, flags=16)) == -1
+    assert _fwd(acc.make_desc(**ok, flags=1 << 8)) == -1      # subspace iterations belong to the RSVD forward
     assert _bwd(acc.make_desc(**ok, flags=acc.ACC_FLAG_SKIP_SKETCH)) == -1
     assert _fwd(acc.make_desc(**ok, flags=acc.ACC_FLAG_ONE_LAUNCH)) in (0, -6)
 

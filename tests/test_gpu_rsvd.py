@@ -72,12 +72,12 @@ def run_rsvd(acc, lin, data, flags=0, factor_dtype=None, dw_dtype=None, want_dw=
     return out
 
 
-def oracle_rsvd(lin, data, seed=None, w_out_in=False):
+def oracle_rsvd(lin, data, seed=None, w_out_in=False, power_iters=0):
     seed = lin.seed if seed is None else seed
     X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
     if w_out_in:
         W = np.ascontiguousarray(W.T)
-    Y, U, V = orc.linear_fwd_rsvd(X, W, seed, lin.r, w_out_in=w_out_in)
+    Y, U, V = orc.linear_fwd_rsvd(X, W, seed, lin.r, w_out_in=w_out_in, power_iters=power_iters)
     dX, Gr, dW = orc.linear_bwd_rsvd(dY, W, U, V, w_out_in=w_out_in)
     cond = np.linalg.cond(X @ orc.range_finder_matrix(seed, lin.d_in, lin.r))
     return {"Y": Y, "dX": dX, "U": U, "V": V, "Gr": Gr, "dW": dW}, cond
@@ -167,3 +167,32 @@ def test_rsvd_strided_operands_and_accumulated_gradient(acc, n, d_in, d_out, k):
     for key in ("Y", "dX", "U", "V", "Gr"):
         assert gu.rel(got[key], want[key]) <= 1e-2, key
     assert gu.rel(got["dW"], start.astype(np.float64) + want["dW"]) <= 1e-2
+
+
+@pytest.mark.parametrize("n,d_in,d_out,k,dtype,q", [
+    (515, 264, 136, 8, "f32", 1),        # generic kernels, float32
+    (777, 520, 264, 32, "bf16", 2),      # generic kernels, bfloat16
+    (1000, 512, 640, 8, "bf16", 1),      # split-K path
+    (4100, 1024, 3080, 32, "bf16", 2),   # split-K path, ragged tokens
+    (3001, 1024, 1544, 48, "bf16", 3),   # rank padded to 64, three rounds
+])
+def test_rsvd_subspace_iterations_against_oracle(acc, n, d_in, d_out, k, dtype, q):
+    """ACC_FLAG_RSVD_POWER_*: q rounds of Z = orth(X^T.U), U = orth(X.Z) after the range finder.  Every
+    product feeding an orthonormalisation runs at fp32-grade precision (hi + lo bf16 parts on the tuned
+    path), so the basis still matches the oracle's to the output rounding."""
+    lin = inputs.Linear(f"rsvd_q{q}_{n}x{d_in}x{d_out}_k{k}", n, d_in, d_out, k, dtype=dtype, seed=6)
+    data = inputs.make(lin)
+    got = run_rsvd(acc, lin, data, flags=q << acc.ACC_FLAG_RSVD_POWER_SHIFT)
+    want, cond = oracle_rsvd(lin, data, power_iters=q)
+    tol = 1e-2 if dtype == "bf16" else max(1e-5, cond * 1e-5)
+    errs = {key: gu.rel(got[key], want[key]) for key in want}
+    errs["orth"] = float(np.linalg.norm(got["U"].T @ got["U"] - np.eye(k)) / np.sqrt(k))
+    print(lin.name, " ".join(f"{a}={b:.2e}" for a, b in errs.items()), flush=True)
+    bad = {a: b for a, b in errs.items() if not b <= tol}
+    assert not bad, (tol, bad)
+    # the iterations do what they are for: the projection error does not grow
+    X = inputs.as_f64(data["X"])
+    plain = run_rsvd(acc, lin, data)
+    e0 = np.linalg.norm(X - plain["U"] @ plain["V"].T)
+    eq = np.linalg.norm(X - got["U"] @ got["V"].T)
+    assert eq <= e0 * 1.001, (eq, e0)
