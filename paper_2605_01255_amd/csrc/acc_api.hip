@@ -719,35 +719,36 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
     if (desc->io_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, 1, L);
     else launch_generic<float, float, float, float, true, true>(p, 1, L);
   }
-  // Orthonormalise with two Cholesky-QR passes (the second removes the loss of orthogonality of the
-  // first), then `power_iters` rounds of subspace iteration: Z = orth(X^T.U), U = orth(X.Z).
+  // The final basis gets two Cholesky-QR passes (the second removes the loss of orthogonality of the
+  // first).  Before it, `power_iters` rounds of subspace iteration: Z = orth(X^T.U), U = orth(X.Z).  The
+  // intermediate bases get ONE pass each: it leaves them orthonormal only to about cond^2 * 2^-24, but any
+  // basis of the form Q.T with T upper triangular gives exactly the same final U (the thin QR of X.Z.T has
+  // the same Q), and one pass is enough to keep the iterates well conditioned.
   for (int it = 0; it <= power_iters; ++it) {
-    const bool last = it == power_iters;
-    cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, y0, q1, nullptr, ACC_F32, nullptr, 0, false, L);
-    if (last) {
+    if (it == power_iters) {
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, y0, q1, nullptr, ACC_F32, nullptr, 0, false, L);
       cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, nullptr, U, desc->factor_dtype, pl.tuned ? ut : nullptr, pl.n_pad,
                        false, L);
       break;
     }
     float* z0 = (float*)(ws + pl.off_z0);
-    float* z1 = (float*)(ws + pl.off_z1);
     if (pl.tuned) {
       // U as hi + lo parts, transposed; Z^T = [U_hi; U_lo] . X over the tokens with the K range split
-      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, nullptr, nullptr, ACC_F32, ut, pl.n_pad, true, L);
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, y0, nullptr, nullptr, ACC_F32, ut, pl.n_pad, true, L);
       float* zt_part = (float*)(ws + pl.off_zt_part);
       const int splits = fast_gemm_splitk<2, 2, 1, 2, false>(ut, X, zt_part, 2 * k, s.d_in, pl.n_pad, pl.n_pad, s.ldx,
                                                            s.d_in, s.n, L);
       L(combine_hilo_t_kernel, dim3((unsigned)ceil_div(k * s.d_in, 256)), dim3(256), (const float*)zt_part, splits,
         s.d_in, (int)k, z0);
-      // orth(Z), the second pass writing it as hi + lo parts [2k, d_in]: the right factor of the next X . Z
-      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, z1, nullptr, ACC_F32, nullptr, 0, false, L);
-      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z1, nullptr, nullptr, ACC_F32, omega, s.d_in, true, L);
+      // orth(Z) written as hi + lo parts [2k, d_in]: the right factor of the next X . Z
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, nullptr, nullptr, ACC_F32, omega, s.d_in, true, L);
       times_hilo();
     } else {
-      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, q1, y0, nullptr, ACC_F32, nullptr, 0, false, L);  // U fp32 -> y0
+      float* z1 = (float*)(ws + pl.off_z1);
+      cholesky_qr_pass(s, pl, ws, s.n, pl.n_pad, y0, q1, nullptr, ACC_F32, nullptr, 0, false, L);  // U fp32 -> q1
       float* part = (float*)(ws + pl.off_fact_part);
       GemmParams g{};  // Z [d_in, k] = X^T . U, token range split
-      g.A = X; g.B = y0; g.C = part;
+      g.A = X; g.B = q1; g.C = part;
       g.M = s.d_in; g.N = k; g.K = s.n;
       g.a_sm = 1; g.a_sk = s.ldx; g.b_sk = k; g.b_sn = 1; g.c_sm = k; g.c_sn = 1;
       g.k_per_split = round_up(ceil_div(s.n, pl.g_fact), 32);
@@ -755,10 +756,9 @@ int acc_linear_fwd_rsvd(const acc_linear_desc* desc, const void* X, const void* 
       const int splits = (int)ceil_div(s.n, g.k_per_split);
       rsvd_gemm(desc->io_dtype, ACC_F32, ACC_F32, g, splits, L);
       reduce_to(ACC_F32, part, splits, s.d_in * k, z0, L);
-      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, z1, nullptr, ACC_F32, nullptr, 0, false, L);
-      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z1, z0, nullptr, ACC_F32, nullptr, 0, false, L);  // orth(Z) -> z0
+      cholesky_qr_pass(s, pl, ws, s.d_in, s.d_in, z0, z1, nullptr, ACC_F32, nullptr, 0, false, L);  // orth(Z) -> z1
       GemmParams y{};  // y0 [n, k] = X . Z
-      y.A = X; y.B = z0; y.C = y0;
+      y.A = X; y.B = z1; y.C = y0;
       y.M = s.n; y.N = k; y.K = s.d_in;
       y.a_sm = s.ldx; y.a_sk = 1; y.b_sk = k; y.b_sn = 1; y.c_sm = k; y.c_sn = 1;
       y.k_per_split = round_up(s.d_in, 32);
