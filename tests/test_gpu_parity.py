@@ -290,3 +290,17 @@ def test_row_offsets_crossing_2_pow_34(acc, n, d_in, d_out, r):
     (tuned 8-wave and 4-wave sketch kernels and the generic one)."""
     lin = inputs.Linear(f"hi_offset_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16", seed=0x5EED5EED5EED)
     _check(acc, lin, row_offset=(1 << 34) - 512)
+
+
+def test_all_zero_inputs_give_exact_zeros(acc):
+    """Degenerate inputs: X = 0 (then Y, Xs, dW are exactly 0) and dY = 0 (then dX, Gr, dW, dB are exactly 0)."""
+    lin = inputs.Linear("zeros", 1000, 512, 640, 128, dtype="bf16")
+    data = inputs.make(lin)
+    zx = dict(data, X=np.zeros_like(data["X"]))
+    got = gu.run_layer(acc, lin, zx)
+    for key in ("Y", "Xs", "dW"):
+        assert np.all(got[key] == 0.0), key
+    zg = dict(data, dY=np.zeros_like(data["dY"]))
+    got = gu.run_layer(acc, lin, zg, want_db=True)
+    for key in ("dX", "Gr", "dW", "dB"):
+        assert np.all(got[key] == 0.0), key

@@ -196,3 +196,16 @@ def test_rsvd_subspace_iterations_against_oracle(acc, n, d_in, d_out, k, dtype, 
     e0 = np.linalg.norm(X - plain["U"] @ plain["V"].T)
     eq = np.linalg.norm(X - got["U"] @ got["V"].T)
     assert eq <= e0 * 1.001, (eq, e0)
+
+
+def test_rsvd_of_an_all_zero_activation_gives_zero_factors_not_nans(acc):
+    """Degenerate input: X = 0 makes X.Omega = 0, every pivot of the Cholesky QR is dropped, U = V = 0,
+    and the weight gradient estimate is 0 (which is X^T.dY)."""
+    lin = inputs.Linear("rsvd_zero", 700, 256, 128, 16, dtype="bf16", seed=2)
+    data = inputs.make(lin)
+    data["X"] = np.zeros_like(data["X"])
+    for q in (0, 1):
+        got = run_rsvd(acc, lin, data, flags=q << acc.ACC_FLAG_RSVD_POWER_SHIFT)
+        for key in ("U", "V", "Gr", "dW", "Y"):
+            assert np.all(got[key] == 0.0), (q, key)
+        assert np.all(np.isfinite(got["dX"]))
