@@ -1,0 +1,117 @@
+"""The operator-level workflow of Def. 3.1 as a PyTorch autograd function and module.
+
+Forward: the output is exact, the input is compressed and only the compressed form is saved for the
+backward pass.  Backward: the input gradient is exact (Thm 3.2.2(a)), the weight gradient is the factored
+estimate of Sec. 4, materialised because `weight.grad` is a dense tensor (update strategy (i)).
+
+Everything numerical happens in libacc's kernels through `binding`; this file only allocates the output
+tensors with torch and keeps the saved factors on the autograd context.  There is no fallback: without the
+library, importing `binding` raises.
+"""
+from __future__ import annotations
+
+import itertools
+
+import torch
+
+from . import binding as acc
+
+_CODES = {torch.bfloat16: acc.ACC_BF16, torch.float32: acc.ACC_F32}
+
+
+def _workspace(nbytes: int, device):
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+class CompressedLinearFunction(torch.autograd.Function):
+    """y = x @ weight.T (+ bias) with `weight` in torch.nn.Linear's [out_features, in_features] layout.
+
+    compressor "rp": the seeded Gaussian token sketch (unbiased; keeps Xs [in_features, rank] + the seed);
+    compressor "rsvd": randomized range finder + projection (keeps U [tokens, rank] and V [in_features, rank]).
+    `seed` must differ from call to call for the random projection to be unbiased over a training run.
+    Linears that share an input (q/k/v, gate/up; Sec. 5.1) are compressed once by stacking their weights
+    into one call.
+    """
+
+    @staticmethod
+    def forward(ctx, x, weight, bias, rank: int, seed: int, compressor: str = "rp", power_iters: int = 0):
+        if x.dtype not in _CODES or weight.dtype != x.dtype:
+            raise TypeError("x and weight must both be bfloat16 or both float32")
+        d_out, d_in = weight.shape
+        x2 = x.reshape(-1, d_in)
+        if not x2.is_contiguous():
+            x2 = x2.contiguous()
+        w = weight if weight.is_contiguous() else weight.contiguous()
+        n, code, dev = x2.shape[0], _CODES[x.dtype], x.device
+        flags = acc.ACC_FLAG_W_OUT_IN
+        y = torch.empty(n, d_out, dtype=x.dtype, device=dev)
+        if compressor == "rp":
+            desc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code, flags=flags)
+            xs = torch.empty(d_in, rank, dtype=x.dtype, device=dev)
+            acc.acc_linear_fwd(desc, x2, w, y, xs, _workspace(acc.acc_linear_workspace_bytes(desc, False), dev))
+            ctx.save_for_backward(w, xs)
+        elif compressor == "rsvd":
+            desc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code,
+                                 flags=flags | (int(power_iters) << acc.ACC_FLAG_RSVD_POWER_SHIFT))
+            u = torch.empty(n, rank, dtype=x.dtype, device=dev)
+            v = torch.empty(d_in, rank, dtype=x.dtype, device=dev)
+            acc.acc_linear_fwd_rsvd(desc, x2, w, y, u, v, _workspace(acc.acc_rsvd_workspace_bytes(desc, False), dev))
+            ctx.save_for_backward(w, u, v)
+        else:
+            raise ValueError("compressor must be 'rp' or 'rsvd'")
+        if bias is not None:
+            y += bias
+        ctx.meta = (compressor, n, d_in, d_out, rank, seed, code, bias is not None, x.shape)
+        return y.reshape(*x.shape[:-1], d_out)
+
+    @staticmethod
+    def backward(ctx, dy):
+        compressor, n, d_in, d_out, rank, seed, code, has_bias, x_shape = ctx.meta
+        dy2 = dy.reshape(n, d_out)
+        if not dy2.is_contiguous():
+            dy2 = dy2.contiguous()
+        dev, dt = dy.device, dy.dtype
+        dx = torch.empty(n, d_in, dtype=dt, device=dev)
+        gr = torch.empty(d_out, rank, dtype=dt, device=dev)
+        dw = torch.empty(d_out, d_in, dtype=dt, device=dev)
+        desc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code, flags=acc.ACC_FLAG_W_OUT_IN)
+        if compressor == "rp":
+            w, xs = ctx.saved_tensors
+            ws = _workspace(acc.acc_linear_workspace_bytes(desc, True), dev)
+            acc.acc_linear_bwd(desc, dy2, w, xs, dx, gr, dw, ws)
+        else:
+            w, u, v = ctx.saved_tensors
+            ws = _workspace(max(acc.acc_rsvd_workspace_bytes(desc, True), acc.acc_linear_workspace_bytes(desc, True)), dev)
+            acc.acc_linear_bwd_rsvd(desc, dy2, w, u, v, dx, gr, dw, ws)
+        db = None
+        if has_bias:
+            db = torch.empty(d_out, dtype=dt, device=dev)
+            bdesc = acc.make_desc(n, d_in, d_out, max(16, (rank + 15) // 16 * 16), seed=seed, io_dtype=code)
+            acc.acc_linear_bias_grad(bdesc, dy2, db, _workspace(acc.acc_linear_workspace_bytes(bdesc, True), dev))
+        return dx.reshape(x_shape), dw, db, None, None, None, None
+
+
+class CompressedLinear(torch.nn.Module):
+    """Drop-in for torch.nn.Linear (same parameter names and layout) that keeps only the compressed input
+    for the backward pass.  Each forward call draws a fresh sketch seed from a per-module counter."""
+
+    def __init__(self, in_features: int, out_features: int, rank: int, bias: bool = True, compressor: str = "rp",
+                 seed: int = 0, power_iters: int = 0, device=None, dtype=torch.bfloat16):
+        super().__init__()
+        self.in_features, self.out_features, self.rank = in_features, out_features, rank
+        self.compressor, self.power_iters = compressor, power_iters
+        self.weight = torch.nn.Parameter(torch.empty(out_features, in_features, device=device, dtype=dtype))
+        if bias:
+            self.bias = torch.nn.Parameter(torch.zeros(out_features, device=device, dtype=dtype))
+        else:
+            self.register_parameter("bias", None)
+        torch.nn.init.normal_(self.weight, std=0.02)
+        self._seeds = itertools.count(int(seed) << 20)
+
+    def forward(self, x):
+        return CompressedLinearFunction.apply(x, self.weight, self.bias, self.rank, next(self._seeds),
+                                              self.compressor, self.power_iters)
+
+    def extra_repr(self):
+        return (f"in_features={self.in_features}, out_features={self.out_features}, rank={self.rank}, "
+                f"compressor={self.compressor}, bias={self.bias is not None}")

@@ -1,0 +1,91 @@
+"""The autograd wrapper (operator workflow of Def. 3.1) against the oracle and against exact PyTorch autograd."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import acc_oracle as orc
+
+
+@pytest.fixture(scope="module")
+def mods():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_01255_amd import autograd as ag
+    return torch, ag
+
+
+def _f64(t):
+    return t.detach().to("cpu").double().numpy()
+
+
+def _rel(a, b):
+    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+
+
+@pytest.mark.parametrize("compressor,rank", [("rp", 64), ("rsvd", 16)])
+def test_module_matches_oracle_and_saves_only_the_factors(mods, compressor, rank):
+    torch, ag = mods
+    torch.manual_seed(0)
+    b, t, d_in, d_out = 4, 300, 512, 384
+    lin = ag.CompressedLinear(d_in, d_out, rank, bias=True, compressor=compressor, seed=3, device="cuda")
+    with torch.no_grad():
+        lin.bias.normal_(std=0.1)
+    x = torch.randn(b, t, d_in, device="cuda", dtype=torch.bfloat16, requires_grad=True)
+    saved = []
+    with torch.autograd.graph.saved_tensors_hooks(lambda z: (saved.append(tuple(z.shape)), z)[1], lambda z: z):
+        y = lin(x)
+    g = (torch.randn_like(y) * 0.01)
+    y.backward(g)
+    # what autograd keeps: the weight and the rank-r factors, never the [tokens, d_in] activation
+    assert (b * t, d_in) not in saved and (b, t, d_in) not in saved, saved
+    assert (d_in, rank) in saved
+
+    X, W, B, dY = _f64(x).reshape(-1, d_in), _f64(lin.weight), _f64(lin.bias), _f64(g).reshape(-1, d_out)
+    seed = 3 << 20
+    if compressor == "rp":
+        Y, Xs = orc.linear_fwd(X, W, seed, rank, w_out_in=True)
+        dX, _, dW = orc.linear_bwd(dY, W, Xs, seed, rank, w_out_in=True)
+    else:
+        Y, U, V = orc.linear_fwd_rsvd(X, W, seed, rank, w_out_in=True)
+        dX, _, dW = orc.linear_bwd_rsvd(dY, W, U, V, w_out_in=True)
+    assert _rel(_f64(y).reshape(-1, d_out), Y + B) <= 1e-2
+    assert _rel(_f64(x.grad).reshape(-1, d_in), dX) <= 1e-2
+    assert _rel(_f64(lin.weight.grad), dW) <= 1e-2
+    assert _rel(_f64(lin.bias.grad), orc.bias_grad(dY)) <= 1e-2
+
+
+def test_input_gradient_equals_exact_autograd_and_weight_gradient_is_unbiased(mods):
+    """dX is the exact layer's (Thm 3.2.2(a)); the mean of the weight gradient over fresh seeds approaches
+    the exact one (Thm 3.2.1(a))."""
+    torch, ag = mods
+    torch.manual_seed(1)
+    n, d_in, d_out, rank = 2048, 256, 128, 64
+    lin = ag.CompressedLinear(d_in, d_out, rank, bias=False, seed=7, device="cuda", dtype=torch.float32)
+    x = torch.randn(n, d_in, device="cuda", requires_grad=True)
+    g = torch.randn(n, d_out, device="cuda") * 0.01
+    xe = x.detach().clone().requires_grad_(True)
+    we = lin.weight.detach().clone().requires_grad_(True)
+    torch.nn.functional.linear(xe, we).backward(g)
+    acc_dw = torch.zeros_like(lin.weight)
+    reps = 200
+    for i in range(reps):
+        lin.weight.grad = None
+        x.grad = None
+        lin(x).backward(g)
+        acc_dw += lin.weight.grad
+        if i == 0:
+            assert _rel(_f64(x.grad), _f64(xe.grad)) <= 1e-5
+            single = _rel(_f64(lin.weight.grad), _f64(we.grad))
+    mean_err = _rel(_f64(acc_dw / reps), _f64(we.grad))
+    assert mean_err < single / 8, (single, mean_err)      # 1/sqrt(200) = 1/14 expected
+
+
+def test_state_dict_is_interchangeable_with_nn_linear(mods):
+    torch, ag = mods
+    ref = torch.nn.Linear(64, 48, bias=True, device="cuda", dtype=torch.bfloat16)
+    lin = ag.CompressedLinear(64, 48, 16, bias=True, device="cuda")
+    lin.load_state_dict(ref.state_dict())
+    x = torch.randn(100, 64, device="cuda", dtype=torch.bfloat16)
+    assert torch.allclose(lin(x).float(), ref(x).float(), atol=2e-2, rtol=2e-2)
