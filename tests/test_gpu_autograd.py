@@ -89,3 +89,34 @@ def test_state_dict_is_interchangeable_with_nn_linear(mods):
     lin.load_state_dict(ref.state_dict())
     x = torch.randn(100, 64, device="cuda", dtype=torch.bfloat16)
     assert torch.allclose(lin(x).float(), ref(x).float(), atol=2e-2, rtol=2e-2)
+
+
+def test_a_small_network_trains_with_compressed_linears(mods):
+    """End to end: a two-layer network on a synthetic regression task, AdamW, compressed vs exact linears.
+    The paper's point (Thm 3.2.1(a), Sec. 5.1): unbiased compression of linear-layer activations barely
+    changes the optimisation.  Loose thresholds: both runs must learn, and end within 2x of each other."""
+    torch, ag = mods
+
+    def run(make_linear):
+        torch.manual_seed(0)
+        d, h, n = 128, 256, 4096
+        teacher = torch.nn.Sequential(torch.nn.Linear(d, h), torch.nn.SiLU(), torch.nn.Linear(h, d)).cuda()
+        net = torch.nn.Sequential(make_linear(d, h), torch.nn.SiLU(), make_linear(h, d)).cuda()
+        opt = torch.optim.AdamW(net.parameters(), lr=2e-3, weight_decay=0.0)
+        losses = []
+        for step in range(150):
+            x = torch.randn(n, d, device="cuda")
+            with torch.no_grad():
+                y = teacher(x)
+            loss = torch.nn.functional.mse_loss(net(x), y)
+            opt.zero_grad(set_to_none=True)
+            loss.backward()
+            opt.step()
+            losses.append(float(loss.detach()))
+        return losses
+
+    exact = run(lambda i, o: torch.nn.Linear(i, o))
+    comp = run(lambda i, o: ag.CompressedLinear(i, o, rank=64, bias=True, dtype=torch.float32, seed=5))
+    print("exact", exact[0], exact[-1], "compressed", comp[0], comp[-1], flush=True)
+    assert exact[-1] < exact[0] / 5 and comp[-1] < comp[0] / 5
+    assert comp[-1] < 2.0 * exact[-1] + 1e-4
