@@ -35,7 +35,26 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def build_c_client(verbose: bool = True) -> str:
+    """The plain-C client of the ABI under tests/c_client (host code only: gcc-style compile through hipcc,
+    linked against the HIP runtime and libacc.so, found at run time next to this package)."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "c_client", "acc_client.c")
+    exe = os.path.join(root, "tests", "c_client", "acc_client")
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-x", "c", "-O2", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", src, "-o", exe,
+           "-L" + HERE, "-lacc", "-L/opt/rocm/lib", "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../../paper_2605_01255_amd", "-Wl,-rpath,/opt/rocm/lib"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("C client build failed:\n" + res.stdout + res.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     build()
     print("built", LIB)
+    build_c_client()
     sys.exit(0)
