@@ -47,7 +47,7 @@ enum {
   ACC_OK = 0,
   ACC_ERR_INVALID_ARG = -1, /* NULL descriptor or required pointer, unknown flag            */
   ACC_ERR_SHAPE = -2,       /* a size is <= 0 or above its limit (n <= 2^30, d_in, d_out <= 2^21,
-                               r <= 2^16), r % 16 != 0, d_in % 8 or d_out % 8 != 0,
+                               r <= 2^16), r % 8 != 0, d_in % 8 or d_out % 8 != 0,
                                a row stride smaller than the row or not a multiple of 8,
                                row_offset % 4 != 0                                           */
   ACC_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                              */
@@ -83,7 +83,7 @@ typedef struct acc_linear_desc {
   int64_t n;            /* tokens (batch x sequence)                                         */
   int64_t d_in;         /* input features,  multiple of 8                                    */
   int64_t d_out;        /* output features, multiple of 8                                    */
-  int64_t r;            /* sketch rank, multiple of 16                                       */
+  int64_t r;            /* sketch rank, multiple of 8                                        */
   int64_t ldx;          /* row stride of X and dX in elements; 0 = d_in                      */
   int64_t ldw;          /* row stride of W in elements;        0 = d_out (d_in with W_OUT_IN) */
   int64_t ldy;          /* row stride of Y and dY in elements; 0 = d_out                     */

@@ -86,7 +86,7 @@ class CompressedLinearFunction(torch.autograd.Function):
         db = None
         if has_bias:
             db = torch.empty(d_out, dtype=dt, device=dev)
-            bdesc = acc.make_desc(n, d_in, d_out, max(16, (rank + 15) // 16 * 16), seed=seed, io_dtype=code)
+            bdesc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code)
             acc.acc_linear_bias_grad(bdesc, dy2, db, _workspace(acc.acc_linear_workspace_bytes(bdesc, True), dev))
         return dx.reshape(x_shape), dw, db, None, None, None, None
 

@@ -28,7 +28,7 @@ struct Shape {
   int64_t n, d_in, d_out, r, ldx, ldw, ldy;
 };
 
-int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16, uint32_t extra_flags = 0) {
+int validate_desc(const acc_linear_desc* d, Shape* s, uint32_t extra_flags = 0) {
   if (!d) return ACC_ERR_INVALID_ARG;
   if (d->flags & ~(uint32_t)(ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_W_OUT_IN | ACC_FLAG_DW_ACCUMULATE |
                              extra_flags))
@@ -36,7 +36,7 @@ int validate_desc(const acc_linear_desc* d, Shape* s, int r_multiple = 16, uint3
   if (!valid_dtype(d->io_dtype) || !valid_dtype(d->factor_dtype) || !valid_dtype(d->dw_dtype))
     return ACC_ERR_DTYPE;
   if (d->n <= 0 || d->d_in <= 0 || d->d_out <= 0 || d->r <= 0) return ACC_ERR_SHAPE;
-  if (d->r % r_multiple || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;
+  if (d->r % 8 || d->d_in % 8 || d->d_out % 8) return ACC_ERR_SHAPE;  // 16-byte rows of every operand and factor
   // limits that keep every grid dimension and 32-bit tile count in range
   if (d->n > (int64_t)1 << 30 || d->d_in > (1 << 21) || d->d_out > (1 << 21) || d->r > (1 << 16))
     return ACC_ERR_SHAPE;
@@ -579,7 +579,7 @@ void dense_dw(const acc_linear_desc* desc, const Shape& s, const void* Xs, const
 }
 
 int validate_rsvd(const acc_linear_desc* d, Shape* s) {
-  const int rc = validate_desc(d, s, 8, 3u << ACC_FLAG_RSVD_POWER_SHIFT);
+  const int rc = validate_desc(d, s, 3u << ACC_FLAG_RSVD_POWER_SHIFT);
   if (rc != ACC_OK) return rc;
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
   if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;

@@ -90,7 +90,7 @@ int main(void) {
       if (e > worst) worst = e;
     }
   /* a refused call must come back as an error code, not a crash */
-  d.r = 24;
+  d.r = 20;
   const int refused = acc_linear_fwd(&d, X, W, Y, Xs, ws, ws_f, NULL);
   printf("worst absolute error %.3g, refused call -> %s\n", worst, acc_status_string(refused));
   if (!(worst < 1e-4) || refused != ACC_ERR_SHAPE) return 1;

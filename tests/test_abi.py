@@ -57,7 +57,7 @@ def _bwd(desc, dY=0x1000, W=0x2000, Xs=0x4000, dX=0x3000, Gr=0x6000, dW=0x7000, 
 def test_invalid_descriptors_are_refused():
     ok = dict(n=256, d_in=256, d_out=512, r=16)
     assert acc._lib.acc_linear_fwd(None, 0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 1 << 30, None) == -1
-    for bad in (dict(n=0), dict(d_in=0), dict(r=0), dict(r=24), dict(d_in=252), dict(d_out=516),
+    for bad in (dict(n=0), dict(d_in=0), dict(r=0), dict(r=20), dict(d_in=252), dict(d_out=516),
                 dict(row_offset=2), dict(ldx=128), dict(ldx=260), dict(ldy=8), dict(n=-5),
                 dict(n=(1 << 30) + 1), dict(d_in=(1 << 21) + 8), dict(r=(1 << 16) + 16)):
         d = acc.make_desc(**{**ok, **bad})

@@ -43,6 +43,9 @@ def test_c1_fp32(acc):
 SHAPES_BF16 = [
     # n, d_in, d_out, r : several tiles plus ragged tails in every dimension
     (512, 512, 768, 64),
+    (1000, 512, 640, 8),        # the paper's smallest rank, tuned kernels (surplus sketch columns masked)
+    (515, 264, 136, 8),         # the same on the generic kernels
+    (2049, 1024, 1544, 24),
     (777, 520, 264, 48),
     (1000, 8, 8, 16),
     (3, 64, 72, 16),
