@@ -28,6 +28,9 @@
  *     allocates, frees or keeps one and never synchronises: a call only enqueues kernels
  *     on `stream` (a hipStream_t passed as void*; NULL = the default stream);
  *   - X, W, Y, dY, dX, Xs, Gr, dW and the workspace must be 16-byte aligned;
+ *   - a workspace is scratch for the duration of a call's kernels: calls that share one must be ordered on
+ *     one stream (or by events); the library is re-entrant otherwise and keeps no state between calls
+ *     except per-kernel launch attributes it sets once;
  *   - return value 0 = success, negative = one of ACC_ERR_*; on error nothing is launched;
  *   - no C++ exception crosses this boundary; the library runs on gfx950 only.
  */
