@@ -296,13 +296,15 @@ SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, in
     sp.G = generic_sketch_splits(n, channels, d->r);
     return sp;
   }
-  if (d->r % 128 == 0) { sp.ch = 512; sp.rc = 128; } else { sp.ch = 1024; sp.rc = 64; }
+  if (d->r % 128 == 0) { sp.ch = 512; sp.rc = 128; }
+  else if (d->r <= 32) { sp.ch = 1024; sp.rc = 32; }  // small ranks (the paper's 8 and 32): half the generated columns
+  else { sp.ch = 1024; sp.rc = 64; }
   sp.n_cslab = (int)ceil_div(channels, sp.ch);
   sp.n_js = (int)ceil_div(d->r, sp.rc);  // the last column slice may be partly empty (rank % 64 != 0)
   int64_t G = (256 + sp.n_cslab * sp.n_js / 2) / (sp.n_cslab * sp.n_js);
   const int64_t max_by_tokens = ceil_div(n, 256);
   if (G > max_by_tokens) G = max_by_tokens;
-  if (G > 32) G = 32;
+  if (G > (sp.rc == 32 ? 64 : 32)) G = sp.rc == 32 ? 64 : 32;  // few, narrow tiles: more token splits fill the chip
   if (G < 1) G = 1;
   sp.tokens_per_split = (int)round_up(ceil_div(n, G), 32);
   sp.G = (int)ceil_div(n, sp.tokens_per_split);
@@ -331,6 +333,10 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
   if (sp.rc == 128) {  // 512 x 128 tile, 8 waves: two waves per SIMD overlap MFMA and Philox (-17 % vs 4 waves)
     if (transposed) L.launch_lds(sketch8_kernel<true>, grid, dim3(512), (size_t)128 * 1024, p);
     else L.launch_lds(sketch8_kernel<false>, grid, dim3(512), (size_t)128 * 1024, p);
+  } else if (sp.rc == 32) {  // 1024 x 32 tile, 4 waves along the channels
+    const size_t lds = sketch_bf16_lds_bytes<4, 1, 8>();
+    if (transposed) L.launch_lds(sketch_bf16_kernel<4, 1, 8, true>, grid, dim3(256), lds, p);
+    else L.launch_lds(sketch_bf16_kernel<4, 1, 8, false>, grid, dim3(256), lds, p);
   } else {             // 1024 x 64 tile, 4 waves
     const size_t lds = sketch_bf16_lds_bytes<2, 2, 16>();
     if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true>, grid, dim3(256), lds, p);

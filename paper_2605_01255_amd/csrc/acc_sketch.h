@@ -167,7 +167,7 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   // the S operand of the following k-step (10 Philox rounds on two counters, 4 Box-Muller pairs, pack).
   // Fences between slots keep this order: the matrix pipe and the vector ALU then run concurrently
   // instead of one after the other, and every LDS read has a whole k-step to return.
-  static_assert(CWB >= 16, "the S generation is spread over 16 slots");
+  static_assert(CWB >= 16 || CWB == 8, "the S generation is spread over 16 slots, or packed into 8");
   struct SGen {
     uint32_t c[2][4];
     float z[8];
@@ -180,15 +180,32 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
         g.c[h][0] = (uint32_t)(q + h); g.c[h][1] = jcol; g.c[h][2] = 0u; g.c[h][3] = (uint32_t)((q + h) >> 32);
       }
     }
-    if (slot < 10) {
-      philox_round(g.c[0], p.sk.key0, p.sk.key1, slot);
-      philox_round(g.c[1], p.sk.key0, p.sk.key1, slot);
-    } else if (slot < 14) {
-      const int pr = slot - 10, h = pr >> 1, a = (pr & 1) * 2;
-      box_muller_fast(g.c[h][a], g.c[h][a + 1], p.sk.neg2_ln2_over_r, g.z[4 * h + a], g.z[4 * h + a + 1]);
-    } else if (slot == 14) {
+    if constexpr (CWB >= 16) {
+      if (slot < 10) {
+        philox_round(g.c[0], p.sk.key0, p.sk.key1, slot);
+        philox_round(g.c[1], p.sk.key0, p.sk.key1, slot);
+      } else if (slot < 14) {
+        const int pr = slot - 10, h = pr >> 1, a = (pr & 1) * 2;
+        box_muller_fast(g.c[h][a], g.c[h][a + 1], p.sk.neg2_ln2_over_r, g.z[4 * h + a], g.z[4 * h + a + 1]);
+      } else if (slot == 14) {
 #pragma unroll
-      for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
+        for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
+      }
+    } else {  // 8 slots: two rounds, then two Box-Muller pairs per slot
+      if (slot < 5) {
+#pragma unroll
+        for (int rr = 2 * slot; rr < 2 * slot + 2; ++rr) {
+          philox_round(g.c[0], p.sk.key0, p.sk.key1, rr);
+          philox_round(g.c[1], p.sk.key0, p.sk.key1, rr);
+        }
+      } else if (slot < 7) {
+        const int h = slot - 5;
+        box_muller_fast(g.c[h][0], g.c[h][1], p.sk.neg2_ln2_over_r, g.z[4 * h], g.z[4 * h + 1]);
+        box_muller_fast(g.c[h][2], g.c[h][3], p.sk.neg2_ln2_over_r, g.z[4 * h + 2], g.z[4 * h + 3]);
+      } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
+      }
     }
   };
   auto kstep_slots = [&](const bf16x8(&af)[CWB], bf16x8 sf, const char* rd_stage, bf16x8(&nf)[CWB], SGen& g,

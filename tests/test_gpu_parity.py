@@ -145,6 +145,8 @@ FAST_SHAPES = [
     (2500, 576, 1096, 64),      # rank-64 sketch tile, ragged channel slab (576 < 1024)
     (8192, 2048, 2048, 192),    # r % 64 == 0 but r % 128 != 0
     (33, 64, 64, 64),           # a single partial stage
+    (4100, 1024, 3080, 32),     # the paper's rank 32: 1024 x 32 sketch tile, up to 64 token splits
+    (20000, 3072, 1024, 16),    # rank 16 with many token splits (G = 64) and three channel slabs
 ]
 
 
