@@ -150,3 +150,18 @@ def test_rsvd_entry_points_validate_the_rank():
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, 0x4000, 0x6000, 0x5000, need - 1, None) == -5
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, None, 0x6000, 0x5000, need, None) == -1
     assert acc.acc_rsvd_workspace_bytes(acc.make_desc(**ok, r=72), False) == 0
+
+
+def test_flag_constants_match_the_header():
+    text = open(HEADER).read()
+    declared = [(m.group(1), int(m.group(2)) << int(m.group(3) or 0))
+                for m in re.finditer(r"\b(ACC_FLAG_[A-Z_0-9]+)\s*=\s*(\d+)u(?:\s*<<\s*(\d+))?", text)]
+    assert len(declared) >= 7
+    for name, value in declared:
+        if hasattr(acc, name):
+            assert getattr(acc, name) == value, name
+    assert acc.ACC_FLAG_SKIP_SKETCH == 1 and acc.ACC_FLAG_ONE_LAUNCH == 2 and acc.ACC_FLAG_W_OUT_IN == 4
+    assert acc.ACC_FLAG_DW_ACCUMULATE == 8
+    shift = int(re.search(r"#define ACC_FLAG_RSVD_POWER_SHIFT (\d+)", text).group(1))
+    assert acc.ACC_FLAG_RSVD_POWER_SHIFT == shift == 8
+    assert re.search(r"ACC_F32 = 0, ACC_BF16 = 1", text) and (acc.ACC_F32, acc.ACC_BF16) == (0, 1)

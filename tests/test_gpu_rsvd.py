@@ -209,3 +209,21 @@ def test_rsvd_of_an_all_zero_activation_gives_zero_factors_not_nans(acc):
         for key in ("U", "V", "Gr", "dW", "Y"):
             assert np.all(got[key] == 0.0), (q, key)
         assert np.all(np.isfinite(got["dX"]))
+
+
+def test_rsvd_backward_with_the_gradient_left_factored(acc):
+    """dW == NULL and V == NULL: only dX and the small factor Gr are produced (Sec. 4: the gradient can stay
+    in factored form)."""
+    import torch
+    lin = inputs.Linear("rsvd_factored", 1200, 512, 384, 32, dtype="bf16", seed=8)
+    data = inputs.make(lin)
+    full = run_rsvd(acc, lin, data)
+    dev = "cuda:0"
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=8, io_dtype=acc.ACC_BF16)
+    dY, W = acc.to_device(data["dY"], dev), acc.to_device(data["W"], dev)
+    U = torch.from_numpy(full["U"]).to(dev).to(torch.bfloat16)
+    dX = torch.empty(lin.n, lin.d_in, dtype=torch.bfloat16, device=dev)
+    Gr = torch.empty(lin.r, lin.d_out, dtype=torch.bfloat16, device=dev)
+    acc.acc_linear_bwd_rsvd(desc, dY, W, U, None, dX, Gr, None, acc.alloc_workspace(desc, True, dev, rsvd=True))
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.to_host_f64(dX), full["dX"]) and np.array_equal(acc.to_host_f64(Gr), full["Gr"])
