@@ -8,6 +8,7 @@ What it computes (spec notation; the paper's is in brackets):
             Gr = S^T . dY             small gradient factor   [Sec. 4: ((grad_Z L)^T U)^T]
             dW = Xs . Gr              factored weight grad    [Sec. 4: G^_W = ((grad_Z L)^T U) V^T, transposed]
             dB = 1^T . dY             bias gradient, exact    [proof of Thm 3.2.2, bias term]
+  update    W <- W - lr left . Adam(Gr)   optimizer strategy (ii), states on the small factor  [Sec. 4]
   With w_out_in=True W, Gr and dW are in the paper's own orientation ([d_out, d_in], [d_out, r]).
 
 S is the n x r random-projection compressor (the paper's "RP" option, Experimental
@@ -37,7 +38,10 @@ term); the 1/sqrt(r) error law matching the paper's RP error table; dX independe
 of seed and rank (Thm 3.2.2(a)); the bias gradient against a finite difference of the
 affine layer's loss; the [d_out, d_in] orientation against index loops in the paper's form;
 the RSVD factors against exact-fraction Gram-Schmidt, exact recovery of low-rank inputs, the
-Eckart-Young lower bound and the projection identities.  No function here is "parity unpinned".
+Eckart-Young lower bound and the projection identities; the low-rank optimizer step against torch's AdamW
+run on a parameter of the small factor's shape, the sign-descent closed form of its first step and dense
+AdamW when the left factor is the identity.  No function here is "parity unpinned"; what the pins of
+lowrank_adamw_step fix is the arithmetic of the stated reading, the reading itself is not in the paper.
 """
 from __future__ import annotations
 
@@ -234,6 +238,36 @@ def bias_grad(dY):
     therefore exact under compression; summed over the tokens that share b it is the column sum of dY.
     """
     return np.sum(np.asarray(dY, dtype=np.float64), axis=0)
+
+
+def lowrank_adamw_step(W, left, Gr, M, V, step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999,
+                       eps: float = 1e-8, weight_decay: float = 0.0, scale: float = 1.0, w_out_in: bool = False):
+    """Optimizer strategy (ii) of Sec. 4: the update is taken from the factored gradient, with the optimizer
+    states kept at the size of the small factor.  The paper names the scheme (the low-rank projected Adam of
+    Zhao et al., ICML 2024) and gives no formulas; the reading used here maps that scheme onto the two factors
+    the backward pass returns, G^_W = left . Gr:
+
+      the small factor Gr [r, d_out] is the projected gradient, the left factor (Xs, or V of the RSVD
+      compressor) [d_in, r] is the projector that carries the normalised step back to weight space;
+
+        M <- beta1 M + (1 - beta1) Gr                    first moment,  [r, d_out]
+        V <- beta2 V + (1 - beta2) Gr o Gr               second moment, [r, d_out]
+        N  = (M / (1 - beta1^step)) / (sqrt(V / (1 - beta2^step)) + eps)      step counted from 1
+        W <- (1 - lr weight_decay) W - lr scale (left . N)                    decoupled weight decay
+
+    With w_out_in the operands are in the paper's orientation: W [d_out, d_in], Gr / M / V / N [d_out, r],
+    and the last line reads W <- (1 - lr weight_decay) W - lr scale (N . left^T).
+    Returns (W_new, M_new, V_new, N), all float64.
+    """
+    W, left, Gr, M, V = (np.asarray(a, dtype=np.float64) for a in (W, left, Gr, M, V))
+    M_new = beta1 * M + (1.0 - beta1) * Gr
+    V_new = beta2 * V + (1.0 - beta2) * Gr * Gr
+    m_hat = M_new / (1.0 - beta1 ** step)
+    v_hat = V_new / (1.0 - beta2 ** step)
+    N = m_hat / (np.sqrt(v_hat) + eps)
+    step_dir = np.matmul(N, left.T) if w_out_in else np.matmul(left, N)
+    W_new = (1.0 - lr * weight_decay) * W - lr * scale * step_dir
+    return W_new, M_new, V_new, N
 
 
 def reconstruct_activation(Xs, seed: int, n: int, r: int, row_offset: int = 0, S=None):
