@@ -8,7 +8,7 @@ What it computes (spec notation; the paper's is in brackets):
             Gr = S^T . dY             small gradient factor   [Sec. 4: ((grad_Z L)^T U)^T]
             dW = Xs . Gr              factored weight grad    [Sec. 4: G^_W = ((grad_Z L)^T U) V^T, transposed]
             dB = 1^T . dY             bias gradient, exact    [proof of Thm 3.2.2, bias term]
-  update    W <- W - lr left . Adam(Gr)   optimizer strategy (ii), states on the small factor  [Sec. 4]
+  update    W <- W - lr P . Adam(P^T left Gr)   optimizer strategy (ii), states at the projected size  [Sec. 4]
   With w_out_in=True W, Gr and dW are in the paper's own orientation ([d_out, d_in], [d_out, r]).
 
 S is the n x r random-projection compressor (the paper's "RP" option, Experimental
@@ -39,8 +39,10 @@ of seed and rank (Thm 3.2.2(a)); the bias gradient against a finite difference o
 affine layer's loss; the [d_out, d_in] orientation against index loops in the paper's form;
 the RSVD factors against exact-fraction Gram-Schmidt, exact recovery of low-rank inputs, the
 Eckart-Young lower bound and the projection identities; the low-rank optimizer step against torch's AdamW
-run on a parameter of the small factor's shape, the sign-descent closed form of its first step and dense
-AdamW when the left factor is the identity.  No function here is "parity unpinned"; what the pins of
+run on a parameter of the small factor's shape, the sign-descent closed form of its first step, dense
+AdamW when the left factor is the identity and AdamW in rotated coordinates when the projector is a square
+orthogonal matrix; the gradient projector through orthonormality, the range identities at full and at
+deficient rank, and the sign convention.  No function here is "parity unpinned"; what the pins of
 lowrank_adamw_step fix is the arithmetic of the stated reading, the reading itself is not in the paper.
 """
 from __future__ import annotations
@@ -240,33 +242,65 @@ def bias_grad(dY):
     return np.sum(np.asarray(dY, dtype=np.float64), axis=0)
 
 
+def gradient_projector(left, Gr, seed: int, k: int, Omega=None, w_out_in: bool = False):
+    """Projector P [d_in, k] of the low-rank optimizer (Sec. 4, update strategy (ii)): an orthonormal basis
+    of a k-dimensional subspace of the range of the factored gradient G^_W = left . Gr [d_in, d_out], found
+    without forming it: randomized range finder (Halko et al.) on the factors,
+
+        Yp = left . (Gr . Omega),  Omega [d_out, k] i.i.d. normals addressed by (seed, output channel, column),
+        P  = the orthonormal factor of the thin QR of Yp, diagonal of the triangular factor positive.
+
+    The scheme the paper points to takes the leading k left singular vectors of the gradient; for k = r (and in
+    general whenever rank(G^_W) <= k) both span exactly range(G^_W), otherwise the range finder's subspace
+    captures it up to the usual randomized-SVD error.  The basis within the subspace differs (QR instead of
+    singular vectors); the paper fixes neither.
+    """
+    left, Gr = np.asarray(left, dtype=np.float64), np.asarray(Gr, dtype=np.float64)
+    if w_out_in:
+        Gr = Gr.T
+    if Omega is None:
+        Omega = range_finder_matrix(seed, Gr.shape[1], k)
+    P, _ = orthonormal_basis(np.matmul(left, np.matmul(Gr, Omega)))
+    return P
+
+
 def lowrank_adamw_step(W, left, Gr, M, V, step: int, lr: float, beta1: float = 0.9, beta2: float = 0.999,
-                       eps: float = 1e-8, weight_decay: float = 0.0, scale: float = 1.0, w_out_in: bool = False):
+                       eps: float = 1e-8, weight_decay: float = 0.0, scale: float = 1.0, w_out_in: bool = False,
+                       P=None):
     """Optimizer strategy (ii) of Sec. 4: the update is taken from the factored gradient, with the optimizer
-    states kept at the size of the small factor.  The paper names the scheme (the low-rank projected Adam of
-    Zhao et al., ICML 2024) and gives no formulas; the reading used here maps that scheme onto the two factors
-    the backward pass returns, G^_W = left . Gr:
+    states kept in a compressed low-rank form.  The paper names the scheme (the low-rank projected Adam of
+    Zhao et al., ICML 2024) and gives no formulas; the reading used here is that scheme applied to the two
+    factors the backward pass returns, G^_W = left . Gr, never forming their product:
 
-      the small factor Gr [r, d_out] is the projected gradient, the left factor (Xs, or V of the RSVD
-      compressor) [d_in, r] is the projector that carries the normalised step back to weight space;
-
-        M <- beta1 M + (1 - beta1) Gr                    first moment,  [r, d_out]
-        V <- beta2 V + (1 - beta2) Gr o Gr               second moment, [r, d_out]
+        R  = P^T G^_W = (P^T left) . Gr                  projected gradient, [k, d_out]; P [d_in, k] is held
+                                                         fixed between refreshes (gradient_projector)
+        M <- beta1 M + (1 - beta1) R                     first moment,  [k, d_out]
+        V <- beta2 V + (1 - beta2) R o R                 second moment, [k, d_out]
         N  = (M / (1 - beta1^step)) / (sqrt(V / (1 - beta2^step)) + eps)      step counted from 1
-        W <- (1 - lr weight_decay) W - lr scale (left . N)                    decoupled weight decay
+        W <- (1 - lr weight_decay) W - lr scale (P . N)                       decoupled weight decay
 
-    With w_out_in the operands are in the paper's orientation: W [d_out, d_in], Gr / M / V / N [d_out, r],
-    and the last line reads W <- (1 - lr weight_decay) W - lr scale (N . left^T).
+    P=None takes the left factor itself as the projector (k = r, R = Gr, step direction left . N): the cheapest
+    form, whose moments live in the basis of the current batch's compressor.
+    With w_out_in the operands are in the paper's orientation: W [d_out, d_in], Gr [d_out, r], M / V / N
+    [d_out, k], and the last line reads W <- (1 - lr weight_decay) W - lr scale (N . P^T).
     Returns (W_new, M_new, V_new, N), all float64.
     """
     W, left, Gr, M, V = (np.asarray(a, dtype=np.float64) for a in (W, left, Gr, M, V))
-    M_new = beta1 * M + (1.0 - beta1) * Gr
-    V_new = beta2 * V + (1.0 - beta2) * Gr * Gr
+    if w_out_in:
+        W, Gr, M, V = W.T, Gr.T, M.T, V.T
+    if P is None:
+        back, R = left, Gr
+    else:
+        back = np.asarray(P, dtype=np.float64)
+        R = np.matmul(np.matmul(back.T, left), Gr)
+    M_new = beta1 * M + (1.0 - beta1) * R
+    V_new = beta2 * V + (1.0 - beta2) * R * R
     m_hat = M_new / (1.0 - beta1 ** step)
     v_hat = V_new / (1.0 - beta2 ** step)
     N = m_hat / (np.sqrt(v_hat) + eps)
-    step_dir = np.matmul(N, left.T) if w_out_in else np.matmul(left, N)
-    W_new = (1.0 - lr * weight_decay) * W - lr * scale * step_dir
+    W_new = (1.0 - lr * weight_decay) * W - lr * scale * np.matmul(back, N)
+    if w_out_in:
+        return W_new.T, M_new.T, V_new.T, N.T
     return W_new, M_new, V_new, N
 
 

@@ -66,6 +66,68 @@ def test_identity_left_factor_reduces_to_dense_adamw_with_decoupled_weight_decay
         np.testing.assert_allclose(W, p.detach().numpy(), rtol=1e-10, atol=1e-13)
 
 
+def test_square_orthogonal_projector_is_adamw_in_rotated_coordinates():
+    # P = Q square orthogonal: Z = Q^T W follows dense AdamW with gradients Q^T G (weight decay commutes with Q),
+    # and W = Q Z.  The gradient arrives factored, G = left . Gr, and is never formed by the oracle call.
+    d, d_out, r, lr, wd = 10, 14, 6, 5e-3, 0.05
+    g = np.random.default_rng(21)
+    Q, _ = np.linalg.qr(g.standard_normal((d, d)))
+    W = g.standard_normal((d, d_out))
+    z = torch.tensor(Q.T @ W, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([z], lr=lr, betas=(0.9, 0.99), eps=1e-7, weight_decay=wd)
+    M = np.zeros((d, d_out)); V = np.zeros((d, d_out))
+    for t in range(1, 5):
+        left, Gr = g.standard_normal((d, r)), g.standard_normal((r, d_out))
+        z.grad = torch.from_numpy(Q.T @ (left @ Gr))
+        opt.step()
+        W, M, V, _ = orc.lowrank_adamw_step(W, left, Gr, M, V, step=t, lr=lr, beta1=0.9, beta2=0.99, eps=1e-7,
+                                            weight_decay=wd, P=Q)
+        np.testing.assert_allclose(W, Q @ z.detach().numpy(), rtol=1e-9, atol=1e-12)
+
+
+def test_thin_projector_moves_the_weight_only_inside_its_range():
+    # k < d_in: the update lies in range(P), and the projected gradient is P^T (left . Gr) entry by entry
+    d, d_out, r, k = 12, 9, 6, 3
+    g = np.random.default_rng(22)
+    P, _ = np.linalg.qr(g.standard_normal((d, k)))
+    W, left, Gr = g.standard_normal((d, d_out)), g.standard_normal((d, r)), g.standard_normal((r, d_out))
+    z = np.zeros((k, d_out))
+    W1, M1, _, _ = orc.lowrank_adamw_step(W, left, Gr, z, z, step=1, lr=0.01, beta1=0.5, P=P)
+    dWt = W1 - W
+    np.testing.assert_allclose(P @ (P.T @ dWt), dWt, rtol=1e-10, atol=1e-14)
+    want_R = np.array([[sum(P[c, a] * sum(left[c, j] * Gr[j, o] for j in range(r)) for c in range(d))
+                        for o in range(d_out)] for a in range(k)])
+    np.testing.assert_allclose(M1, 0.5 * want_R, rtol=1e-10, atol=1e-14)
+
+
+def test_gradient_projector_spans_the_gradients_range():
+    g = np.random.default_rng(23)
+    d, d_out, r = 40, 30, 8
+    left, Gr = g.standard_normal((d, r)), g.standard_normal((r, d_out))
+    G = left @ Gr
+    # k = r: exactly the range of the factored gradient, which is also what its r leading singular vectors span
+    P = orc.gradient_projector(left, Gr, seed=5, k=r)
+    np.testing.assert_allclose(P.T @ P, np.eye(r), atol=1e-12)
+    np.testing.assert_allclose(P @ (P.T @ G), G, rtol=1e-9, atol=1e-11)
+    U = np.linalg.svd(G)[0][:, :r]
+    np.testing.assert_allclose(P @ P.T, U @ U.T, atol=1e-10)
+    # rank(G) = 3 < k = 4 <= r: still the whole range
+    Gr3 = g.standard_normal((r, 3)) @ g.standard_normal((3, d_out))
+    P4 = orc.gradient_projector(left, Gr3, seed=5, k=4)
+    np.testing.assert_allclose(P4[:, :3] @ (P4[:, :3].T @ (left @ Gr3)), left @ Gr3, rtol=1e-8, atol=1e-10)
+    # k < rank: orthonormal, inside the range, first column along G . Omega[:, 0] with a positive coefficient
+    P2 = orc.gradient_projector(left, Gr, seed=5, k=2)
+    np.testing.assert_allclose(P2.T @ P2, np.eye(2), atol=1e-12)
+    np.testing.assert_allclose(U @ (U.T @ P2), P2, atol=1e-10)
+    Om = orc.range_finder_matrix(5, d_out, 2)
+    y0 = G @ Om[:, 0]
+    np.testing.assert_allclose(P2[:, 0], y0 / np.linalg.norm(y0), rtol=1e-10, atol=1e-13)
+    # the paper's orientation of Gr gives the same projector
+    np.testing.assert_allclose(orc.gradient_projector(left, Gr.T, seed=5, k=2, w_out_in=True), P2, atol=1e-14)
+    # an explicit Omega replaces the seeded one
+    np.testing.assert_allclose(orc.gradient_projector(left, Gr, seed=0, k=2, Omega=Om), P2, atol=1e-14)
+
+
 def test_paper_orientation_is_the_transpose():
     W, left, Gr = _factors(7)
     g = np.random.default_rng(8)
@@ -74,6 +136,12 @@ def test_paper_orientation_is_the_transpose():
     kw = dict(step=4, lr=0.02, beta1=0.7, beta2=0.9, eps=1e-5, weight_decay=0.05, scale=2.0)
     a = orc.lowrank_adamw_step(W, left, Gr, M, V, **kw)
     b = orc.lowrank_adamw_step(W.T, left, Gr.T, M.T, V.T, w_out_in=True, **kw)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y.T, rtol=1e-13, atol=1e-15)
+    P, _ = np.linalg.qr(g.standard_normal((left.shape[0], 4)))
+    Mk, Vk = M[:4], V[:4]
+    a = orc.lowrank_adamw_step(W, left, Gr, Mk, Vk, P=P, **kw)
+    b = orc.lowrank_adamw_step(W.T, left, Gr.T, Mk.T, Vk.T, w_out_in=True, P=P, **kw)
     for x, y in zip(a, b):
         np.testing.assert_allclose(x, y.T, rtol=1e-13, atol=1e-15)
 
