@@ -128,6 +128,54 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
 int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, void* workspace,
                          size_t ws_bytes, void* stream);
 
+/* ---- Optimizer step on the factored gradient (Sec. 4, update strategy (ii)) ------------------------
+ * The paper names the scheme (optimizer states kept in a compressed low-rank form, in the manner of the
+ * gradient low-rank projection of Zhao et al., ICML 2024) and gives no formulas.  Reading: that scheme applied
+ * to the two factors a backward call returns, G^_W = left . Gr (left = Xs of acc_linear_bwd or V of
+ * acc_linear_bwd_rsvd), whose product is never formed; weight decay is decoupled (AdamW):
+ *   R  = P^T G^_W = (P^T . left) . Gr          projected gradient [k, d_out]; the projector P [d_in, k] has
+ *                                              orthonormal columns and is held fixed between refreshes
+ *   M <- beta1 M + (1 - beta1) R;   V <- beta2 V + (1 - beta2) R o R               (fp32, in place)
+ *   N  = (M / (1 - beta1^step)) / (sqrt(V / (1 - beta2^step)) + eps)               (factor_dtype, workspace)
+ *   W <- (1 - lr weight_decay) W - lr scale (P . N)                                 (io_dtype, in place)
+ * With P == NULL the left factor itself is the projector: k = r, R = Gr, W moves along left . N; the moments
+ * then live in the basis of the current batch's compressor.
+ * Refreshing the projector (acc_lowrank_projector): an orthonormal basis of a k-dimensional subspace of
+ * range(G^_W) by a randomized range finder on the factors,
+ *   Omega [d_out, k] Gaussian, Omega[o, j] = the Philox normal of (seed, token index := o, column j);
+ *   Yp = left . (Gr . Omega);   Yp = P . T, P^T.P = I, diag(T) > 0 (Cholesky QR, applied twice).
+ * For k = r, and whenever rank(G^_W) <= k, range(P) = range(G^_W), which is also what the leading singular
+ * vectors span.  No dense gradient and no dense optimizer state exists at any point. */
+typedef struct acc_adamw_hyper {
+  float lr, beta1, beta2, eps, weight_decay;
+  float scale;     /* multiplies the step taken back to weight space (1 = none)          */
+  int32_t step;    /* number of this update, counted from 1 (bias correction)            */
+  int32_t reserved;/* 0                                                                  */
+} acc_adamw_hyper;
+
+/* Bytes of device workspace of acc_lowrank_adamw_step and acc_lowrank_projector for projector rank k (k == 0:
+ * the step without a projector); 0 = invalid descriptor or k.  Of desc only d_in, d_out, r, ldw, io_dtype,
+ * factor_dtype, seed and ACC_FLAG_W_OUT_IN matter to the three calls (n must be valid; it is not used). */
+size_t acc_lowrank_workspace_bytes(const acc_linear_desc* desc, int64_t k);
+
+/* P [d_in, k] (dense, factor_dtype) is overwritten with the projector of the factored gradient left . Gr.
+ * left [d_in, r] and Gr ([r, d_out], or [d_out, r] under ACC_FLAG_W_OUT_IN), both factor_dtype, are read.
+ * k: multiple of 8, 8 <= k <= 64, k <= r, k <= d_in (else ACC_ERR_SHAPE).  If Yp has dependent columns
+ * (rank(G^_W) < k) the corresponding columns of P are zero. */
+int acc_lowrank_projector(const acc_linear_desc* desc, int64_t k, const void* left, const void* Gr, void* P,
+                          void* workspace, size_t ws_bytes, void* stream);
+
+/* One update of W from the factors of one backward call.  P [d_in, k] (factor_dtype; k a multiple of 8,
+ * k <= d_in; any orthonormal projector, not only acc_lowrank_projector's) or NULL (k ignored), left and Gr as
+ * above are read; M and V (fp32, dense, [k, d_out], or [d_out, k] under ACC_FLAG_W_OUT_IN, with k = r when P is
+ * NULL; zero before step 1) and W ([d_in, ldw], or [d_out, ldw] under ACC_FLAG_W_OUT_IN, io_dtype) are
+ * updated in place.  ACC_ERR_INVALID_ARG also for step < 1, beta outside [0, 1), eps < 0 or a non-finite
+ * lr / weight_decay / scale, and for ACC_FLAG_SKIP_SKETCH, ACC_FLAG_ONE_LAUNCH or ACC_FLAG_DW_ACCUMULATE.
+ * A bf16 W rounds the product P . N to bf16, then the updated weight. */
+int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* hyper, const void* P, int64_t k,
+                           const void* left, const void* Gr, float* M, float* V, void* W, void* workspace,
+                           size_t ws_bytes, void* stream);
+
 /* ---- RSVD compressor (Experimental Setup: randomized SVD of Halko, Martinsson and Tropp; Sec. 4: the
  * compressed activation is kept as two factors, X^ = U.V^T, U [n, r], V [d_in, r]) -------------------
  * Reading (the paper fixes only the rank): randomized range finder and projection, no oversampling, no

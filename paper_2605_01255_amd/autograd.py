@@ -2,7 +2,8 @@
 
 Forward: the output is exact, the input is compressed and only the compressed form is saved for the
 backward pass.  Backward: the input gradient is exact (Thm 3.2.2(a)), the weight gradient is the factored
-estimate of Sec. 4, materialised because `weight.grad` is a dense tensor (update strategy (i)).
+estimate of Sec. 4, materialised because `weight.grad` is a dense tensor (update strategy (i)), or, with
+`factored_grad=True`, left as its two factors for `LowRankAdamW` (update strategy (ii)).
 
 Everything numerical happens in libacc's kernels through `binding`; this file only allocates the output
 tensors with torch and keeps the saved factors on the autograd context.  There is no fallback: without the
@@ -34,7 +35,8 @@ class CompressedLinearFunction(torch.autograd.Function):
     """
 
     @staticmethod
-    def forward(ctx, x, weight, bias, rank: int, seed: int, compressor: str = "rp", power_iters: int = 0):
+    def forward(ctx, x, weight, bias, rank: int, seed: int, compressor: str = "rp", power_iters: int = 0,
+                factor_sink=None):
         if x.dtype not in _CODES or weight.dtype != x.dtype:
             raise TypeError("x and weight must both be bfloat16 or both float32")
         d_out, d_in = weight.shape
@@ -62,6 +64,7 @@ class CompressedLinearFunction(torch.autograd.Function):
         if bias is not None:
             y += bias
         ctx.meta = (compressor, n, d_in, d_out, rank, seed, code, bias is not None, x.shape)
+        ctx.factor_sink = factor_sink
         return y.reshape(*x.shape[:-1], d_out)
 
     @staticmethod
@@ -73,22 +76,27 @@ class CompressedLinearFunction(torch.autograd.Function):
         dev, dt = dy.device, dy.dtype
         dx = torch.empty(n, d_in, dtype=dt, device=dev)
         gr = torch.empty(d_out, rank, dtype=dt, device=dev)
-        dw = torch.empty(d_out, d_in, dtype=dt, device=dev)
+        sink = ctx.factor_sink
+        dw = None if sink is not None else torch.empty(d_out, d_in, dtype=dt, device=dev)
         desc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code, flags=acc.ACC_FLAG_W_OUT_IN)
         if compressor == "rp":
             w, xs = ctx.saved_tensors
             ws = _workspace(acc.acc_linear_workspace_bytes(desc, True), dev)
             acc.acc_linear_bwd(desc, dy2, w, xs, dx, gr, dw, ws)
+            left = xs
         else:
             w, u, v = ctx.saved_tensors
             ws = _workspace(max(acc.acc_rsvd_workspace_bytes(desc, True), acc.acc_linear_workspace_bytes(desc, True)), dev)
             acc.acc_linear_bwd_rsvd(desc, dy2, w, u, v, dx, gr, dw, ws)
+            left = v
+        if sink is not None:   # the weight gradient stays factored: left [d_in, r], gr [d_out, r]
+            sink.grad_factors = (left, gr)
         db = None
         if has_bias:
             db = torch.empty(d_out, dtype=dt, device=dev)
             bdesc = acc.make_desc(n, d_in, d_out, rank, seed=seed, io_dtype=code)
             acc.acc_linear_bias_grad(bdesc, dy2, db, _workspace(acc.acc_linear_workspace_bytes(bdesc, True), dev))
-        return dx.reshape(x_shape), dw, db, None, None, None, None
+        return dx.reshape(x_shape), dw, db, None, None, None, None, None
 
 
 class CompressedLinear(torch.nn.Module):
@@ -96,8 +104,10 @@ class CompressedLinear(torch.nn.Module):
     for the backward pass.  Each forward call draws a fresh sketch seed from a per-module counter."""
 
     def __init__(self, in_features: int, out_features: int, rank: int, bias: bool = True, compressor: str = "rp",
-                 seed: int = 0, power_iters: int = 0, device=None, dtype=torch.bfloat16):
+                 seed: int = 0, power_iters: int = 0, device=None, dtype=torch.bfloat16, factored_grad: bool = False):
         super().__init__()
+        self.factored_grad = factored_grad
+        self.grad_factors = None   # (left [in, rank], gr [out, rank]) of the last backward pass when factored_grad
         self.in_features, self.out_features, self.rank = in_features, out_features, rank
         self.compressor, self.power_iters = compressor, power_iters
         self.weight = torch.nn.Parameter(torch.empty(out_features, in_features, device=device, dtype=dtype))
@@ -110,8 +120,51 @@ class CompressedLinear(torch.nn.Module):
 
     def forward(self, x):
         return CompressedLinearFunction.apply(x, self.weight, self.bias, self.rank, next(self._seeds),
-                                              self.compressor, self.power_iters)
+                                              self.compressor, self.power_iters,
+                                              self if self.factored_grad else None)
 
     def extra_repr(self):
         return (f"in_features={self.in_features}, out_features={self.out_features}, rank={self.rank}, "
                 f"compressor={self.compressor}, bias={self.bias is not None}")
+
+
+class LowRankAdamW:
+    """Update strategy (ii) of Sec. 4 for `CompressedLinear(..., factored_grad=True)` modules: AdamW whose moments
+    have the shape of the small gradient factor [out_features, rank]; the weights are updated in place by
+    acc_lowrank_adamw_step, and no dense gradient or dense optimizer state is ever allocated.  One backward pass
+    per step (factors of several micro-batches cannot be summed).  Biases are left to an ordinary optimizer.
+    """
+
+    def __init__(self, modules, lr: float = 1e-3, betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0,
+                 scale: float = 1.0):
+        self.modules = [m for m in modules if isinstance(m, CompressedLinear) and m.factored_grad]
+        if not self.modules:
+            raise ValueError("no CompressedLinear module with factored_grad=True")
+        self.lr, self.betas, self.eps, self.weight_decay, self.scale = lr, betas, eps, weight_decay, scale
+        self.state = {}
+
+    @torch.no_grad()
+    def step(self):
+        for m in self.modules:
+            if m.grad_factors is None:
+                continue
+            left, gr = m.grad_factors
+            st = self.state.get(m)
+            if st is None:
+                st = self.state[m] = {"step": 0, "exp_avg": torch.zeros(gr.shape, dtype=torch.float32, device=gr.device),
+                                      "exp_avg_sq": torch.zeros(gr.shape, dtype=torch.float32, device=gr.device)}
+            st["step"] += 1
+            w = m.weight.data
+            if not w.is_contiguous():
+                raise ValueError("weight must be contiguous to be updated in place")
+            desc = acc.make_desc(1, m.in_features, m.out_features, m.rank, io_dtype=_CODES[w.dtype],
+                                 factor_dtype=_CODES[gr.dtype], flags=acc.ACC_FLAG_W_OUT_IN)
+            hyper = acc.make_hyper(st["step"], self.lr, self.betas[0], self.betas[1], self.eps, self.weight_decay,
+                                   self.scale)
+            ws = _workspace(gr.numel() * gr.element_size(), gr.device)
+            acc.acc_lowrank_adamw_step(desc, hyper, None, 0, left, gr, st["exp_avg"], st["exp_avg_sq"], w, ws)
+            m.grad_factors = None
+
+    def zero_grad(self):
+        for m in self.modules:
+            m.grad_factors = None

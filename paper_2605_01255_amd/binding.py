@@ -20,7 +20,9 @@ ACC_FLAG_DW_ACCUMULATE = 8
 ACC_FLAG_RSVD_POWER_SHIFT = 8   # flags bits 8..9: rounds of subspace iteration of the RSVD forward
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
-           "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_philox_dump_u32",
+           "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_lowrank_workspace_bytes",
+           "acc_lowrank_projector", "acc_lowrank_adamw_step",
+           "acc_philox_dump_u32",
            "acc_sketch_dump", "acc_status_string", "acc_version")
 
 
@@ -31,6 +33,13 @@ class AccLinearDesc(ctypes.Structure):
                 ("ldy", ctypes.c_int64), ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
                 ("io_dtype", ctypes.c_int32), ("factor_dtype", ctypes.c_int32),
                 ("dw_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+class AccAdamwHyper(ctypes.Structure):
+    """Mirror of `acc_adamw_hyper`."""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("scale", ctypes.c_float),
+                ("step", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class AccError(RuntimeError):
@@ -63,6 +72,13 @@ _lib.acc_linear_fwd_rsvd.restype = ctypes.c_int
 _lib.acc_linear_fwd_rsvd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_linear_bwd_rsvd.restype = ctypes.c_int
 _lib.acc_linear_bwd_rsvd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_lowrank_adamw_step.restype = ctypes.c_int
+_lib.acc_lowrank_adamw_step.argtypes = [_dp, ctypes.POINTER(AccAdamwHyper), _vp, ctypes.c_int64, _vp, _vp, _vp, _vp,
+                                        _vp, _vp, _sz, _vp]
+_lib.acc_lowrank_workspace_bytes.restype = _sz
+_lib.acc_lowrank_workspace_bytes.argtypes = [_dp, ctypes.c_int64]
+_lib.acc_lowrank_projector.restype = ctypes.c_int
+_lib.acc_lowrank_projector.argtypes = [_dp, ctypes.c_int64, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_philox_dump_u32.restype = ctypes.c_int
 _lib.acc_philox_dump_u32.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64, _vp, _vp]
 _lib.acc_sketch_dump.restype = ctypes.c_int
@@ -160,6 +176,37 @@ def acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, dW, workspace, stream=None, w
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.acc_linear_bwd_rsvd(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(U), _ptr(V), _ptr(dX),
                                     _ptr(Gr), _ptr(dW), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def make_hyper(step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, scale=1.0) -> AccAdamwHyper:
+    return AccAdamwHyper(lr, beta1, beta2, eps, weight_decay, scale, step, 0)
+
+
+def acc_lowrank_workspace_bytes(desc: AccLinearDesc, k: int) -> int:
+    return int(_lib.acc_lowrank_workspace_bytes(ctypes.byref(desc), int(k)))
+
+
+def acc_lowrank_projector(desc, k, left, Gr, P, workspace, stream=None, ws_bytes=None):
+    """Enqueue P [d_in, k] = orthonormal basis of a k-dimensional subspace of range(left . Gr)."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_lowrank_projector(ctypes.byref(desc), int(k), _ptr(left), _ptr(Gr), _ptr(P), _ptr(workspace),
+                                      ws_bytes, _stream(stream)))
+
+
+def acc_lowrank_adamw_step(desc, hyper, P, k, left, Gr, M, V, W, workspace, stream=None, ws_bytes=None):
+    """Enqueue one AdamW update of W from the gradient factors left [d_in, r] and Gr, through the projector
+    P [d_in, k] (None: the left factor is the projector, k = r); M, V fp32 [k, d_out]."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_lowrank_adamw_step(ctypes.byref(desc), ctypes.byref(hyper), _ptr(P), int(k), _ptr(left),
+                                       _ptr(Gr), _ptr(M), _ptr(V), _ptr(W), _ptr(workspace), ws_bytes,
+                                       _stream(stream)))
+
+
+def alloc_lowrank_workspace(desc, k: int, device="cuda:0"):
+    import torch
+    return torch.empty(max(acc_lowrank_workspace_bytes(desc, k), 16), dtype=torch.uint8, device=device)
 
 
 def acc_philox_dump_u32(seed, row_offset, n, r, out, stream=None):

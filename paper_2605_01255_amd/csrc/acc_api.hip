@@ -12,6 +12,7 @@
 #include "acc_fused.h"
 #include "acc_gemm.h"
 #include "acc_generic.h"
+#include "acc_optim.h"
 #include "acc_rsvd.h"
 #include "acc_sketch.h"
 
@@ -181,20 +182,31 @@ void generic_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_
     L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (float*)out);
 }
 
-void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const void* Gr, void* dW, Launcher& L) {
+// Where a product of the two factors goes: the dense gradient, or the weight itself (optimizer step).
+struct FactorProductOut {
+  void* C;
+  int32_t dtype;
+  int64_t ld;          // row stride in elements
+  bool accumulate;     // C = beta C + alpha (product) instead of C = product
+  float alpha, beta;
+};
+
+void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const void* Gr, const FactorProductOut& o,
+                Launcher& L) {
   GemmParams p{};
-  if (d->flags & ACC_FLAG_W_OUT_IN) {  // dW [d_out, d_in] = Gr [d_out, r] . Xs^T
-    p.A = Gr; p.B = Xs; p.C = dW;
+  if (d->flags & ACC_FLAG_W_OUT_IN) {  // [d_out, d_in] = Gr [d_out, r] . Xs^T
+    p.A = Gr; p.B = Xs; p.C = o.C;
     p.M = s.d_out; p.N = s.d_in; p.K = s.r;
-    p.a_sm = s.r; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.r; p.c_sm = s.d_in; p.c_sn = 1;
+    p.a_sm = s.r; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.r; p.c_sm = o.ld; p.c_sn = 1;
   } else {
-    p.A = Xs; p.B = Gr; p.C = dW;
+    p.A = Xs; p.B = Gr; p.C = o.C;
     p.M = s.d_in; p.N = s.d_out; p.K = s.r;
-    p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
+    p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = o.ld; p.c_sn = 1;
   }
   p.k_per_split = round_up(s.r, 32);
-  p.accumulate = (d->flags & ACC_FLAG_DW_ACCUMULATE) ? 1 : 0;
-  const bool fb = d->factor_dtype == ACC_BF16, ob = d->dw_dtype == ACC_BF16;
+  p.accumulate = o.accumulate ? 1 : 0;
+  p.alpha = o.alpha; p.beta = o.beta;
+  const bool fb = d->factor_dtype == ACC_BF16, ob = o.dtype == ACC_BF16;
   if (fb && ob) launch_generic<bf16, bf16, bf16, bf16, false, false>(p, 1, L);
   else if (fb) launch_generic<bf16, bf16, float, bf16, false, false>(p, 1, L);
   else if (ob) launch_generic<float, float, bf16, float, false, true>(p, 1, L);
@@ -222,9 +234,11 @@ struct ReduceJob {
 
 template <bool KMAJ, typename TC>
 void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda,
-               int64_t ldb, int64_t ldc, Launcher& L, const ReduceJob* job = nullptr, bool accumulate = false) {
+               int64_t ldb, int64_t ldc, Launcher& L, const ReduceJob* job = nullptr, bool accumulate = false,
+               float alpha = 1.f, float beta = 1.f) {
   FastGemmParams p{};
   p.accumulate = accumulate ? 1 : 0;
+  p.alpha = alpha; p.beta = beta;
   p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
   p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
   if (job && job->count) {
@@ -569,19 +583,32 @@ void exact_backward_gemm(const acc_linear_desc* desc, const Shape& s, const void
   }
 }
 
-// dW = V . Gr (or Gr . V^T in the paper's orientation): the same product as the random-projection path's.
+// Product of the stored left factor (Xs, or V of the RSVD path) and the small factor, left . Gr (or Gr . left^T in
+// the paper's orientation), written or accumulated into `o`.
+void factor_product(const acc_linear_desc* desc, const Shape& s, const void* Xs, const void* Gr,
+                    const FactorProductOut& o, Launcher& L) {
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
+    if (o.dtype == ACC_BF16)
+      fast_gemm<true, bf16>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.r, s.r, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+    else
+      fast_gemm<true, float>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.r, s.r, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+  } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
+    if (o.dtype == ACC_BF16)
+      fast_gemm<false, bf16>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.r, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+    else
+      fast_gemm<false, float>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.r, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+  } else {
+    generic_dw(desc, s, Xs, Gr, o, L);
+  }
+}
+
+// dW = left . Gr: dense, of desc->dw_dtype, summed into the caller's dW under ACC_FLAG_DW_ACCUMULATE.
 void dense_dw(const acc_linear_desc* desc, const Shape& s, const void* Xs, const void* Gr, void* dW, Launcher& L) {
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  const bool dw_acc = (desc->flags & ACC_FLAG_DW_ACCUMULATE) != 0;
-  if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
-    if (desc->dw_dtype == ACC_BF16) fast_gemm<true, bf16>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
-    else fast_gemm<true, float>(Gr, Xs, dW, s.d_out, s.d_in, s.r, s.r, s.r, s.d_in, L, nullptr, dw_acc);
-  } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
-    if (desc->dw_dtype == ACC_BF16) fast_gemm<false, bf16>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
-    else fast_gemm<false, float>(Xs, Gr, dW, s.d_in, s.d_out, s.r, s.r, s.d_out, s.d_out, L, nullptr, dw_acc);
-  } else {
-    generic_dw(desc, s, Xs, Gr, dW, L);
-  }
+  const FactorProductOut o{dW, desc->dw_dtype, w_oi ? s.d_in : s.d_out, (desc->flags & ACC_FLAG_DW_ACCUMULATE) != 0,
+                           1.f, 1.f};
+  factor_product(desc, s, Xs, Gr, o, L);
 }
 
 int validate_rsvd(const acc_linear_desc* d, Shape* s) {
@@ -590,6 +617,69 @@ int validate_rsvd(const acc_linear_desc* d, Shape* s) {
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
   if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
   return ACC_OK;
+}
+
+// ---- optimizer step on the factored gradient ---------------------------------------------------------
+// k == 0: no separate projector (the left factor is the projector).  for_projector: the orthonormalisation
+// runs on the small-rank Cholesky kernels, which sets the upper limit of k.
+int validate_lowrank(const acc_linear_desc* d, Shape* s, int64_t k, bool for_projector) {
+  const int rc = validate_desc(d, s);
+  if (rc != ACC_OK) return rc;
+  if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
+  if (k < 0 || k % 8 || k > s->d_in || k > (1 << 16)) return ACC_ERR_SHAPE;
+  if (for_projector && (k < 8 || k > kRsvdMaxRank || k > s->r)) return ACC_ERR_SHAPE;
+  return ACC_OK;
+}
+
+struct LowrankPlan {
+  int t1_splits, z_splits, g_gram;
+  int64_t t1_k_per_split, z_k_per_split;
+  size_t off_n, off_part, off_t1, off_r;                                  // the step
+  size_t off_z, off_yp, off_q1, off_gram_part, off_gram, off_rinv;        // the projector (shares off_part)
+  size_t step_total, total;
+};
+
+// Splits of a reduction of length K whose output has `tiles` 64 x 64 tiles: about 512 work-groups, at least 64
+// elements of K each.
+int64_t lowrank_splits(int64_t tiles, int64_t K) {
+  int64_t g = 512 / tiles;
+  if (g > K / 64) g = K / 64;
+  return g < 1 ? 1 : g;
+}
+
+LowrankPlan plan_lowrank(const acc_linear_desc* d, const Shape& s, int64_t k) {
+  LowrankPlan pl{};
+  const size_t fsz = dtype_size(d->factor_dtype);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += (bytes + 255) / 256 * 256; return at; };
+  const int64_t kk = k ? k : s.r;
+  pl.off_n = take((size_t)kk * s.d_out * fsz);
+  if (!k) {
+    pl.step_total = pl.total = off;
+    return pl;
+  }
+  int64_t g = lowrank_splits(ceil_div(k, 64) * ceil_div(s.r, 64), s.d_in);
+  pl.t1_k_per_split = round_up(ceil_div(s.d_in, g), 32);
+  pl.t1_splits = (int)ceil_div(s.d_in, pl.t1_k_per_split);
+  g = lowrank_splits(ceil_div(s.r, 64) * ceil_div(k, 64), s.d_out);
+  pl.z_k_per_split = round_up(ceil_div(s.d_out, g), 32);
+  pl.z_splits = (int)ceil_div(s.d_out, pl.z_k_per_split);
+  const int max_splits = pl.t1_splits > pl.z_splits ? pl.t1_splits : pl.z_splits;
+  pl.off_part = take((size_t)max_splits * k * s.r * 4);
+  pl.off_t1 = take((size_t)k * s.r * 4);
+  pl.off_r = take((size_t)k * s.d_out * 4);
+  pl.step_total = off;
+  if (k <= kRsvdMaxRank && k <= s.r) {
+    pl.g_gram = 256;
+    pl.off_z = take((size_t)s.r * k * 4);
+    pl.off_yp = take((size_t)s.d_in * k * 4);
+    pl.off_q1 = take((size_t)s.d_in * k * 4);
+    pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
+    pl.off_gram = take((size_t)k * k * 4);
+    pl.off_rinv = take((size_t)k * k * 4);
+  }
+  pl.total = off;
+  return pl;
 }
 
 size_t workspace_bytes(const acc_linear_desc* d, const Shape& s, bool backward) {
@@ -833,6 +923,136 @@ int acc_linear_bias_grad(const acc_linear_desc* desc, const void* dY, void* dB, 
     L(colsum_final_kernel<bf16>, dim3(blocks), dim3(256), (const float*)part, (int)G, s.d_out, (bf16*)dB);
   else
     L(colsum_final_kernel<float>, dim3(blocks), dim3(256), (const float*)part, (int)G, s.d_out, (float*)dB);
+  return L.status();
+}
+
+size_t acc_lowrank_workspace_bytes(const acc_linear_desc* desc, int64_t k) {
+  Shape s;
+  if (validate_lowrank(desc, &s, k, false) != ACC_OK) return 0;
+  return plan_lowrank(desc, s, k).total;
+}
+
+int acc_lowrank_projector(const acc_linear_desc* desc, int64_t k, const void* left, const void* Gr, void* P,
+                          void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_lowrank(desc, &s, k, true);
+  if (rc != ACC_OK) return rc;
+  if (!left || !Gr || !P) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(left) || !aligned16(Gr) || !aligned16(P) || !aligned16(workspace)) return ACC_ERR_ALIGN;
+  const LowrankPlan pl = plan_lowrank(desc, s, k);
+  if (!workspace || ws_bytes < pl.total) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  char* ws = (char*)workspace;
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  float* z = (float*)(ws + pl.off_z);
+  float* yp = (float*)(ws + pl.off_yp);
+  float* q1 = (float*)(ws + pl.off_q1);
+  // Z [r, k] = Gr . Omega over the output channels, Omega[o, j] from the Philox map with the channel index in
+  // the token's place, generated in fp32 while it is staged; the channel range split, partials folded by K4
+  {
+    acc_linear_desc od = *desc;
+    od.row_offset = 0;
+    od.r = k;
+    GemmParams p{};
+    p.A = Gr; p.B = nullptr; p.C = ws + pl.off_part;
+    p.M = s.r; p.N = k; p.K = s.d_out;
+    p.a_sm = w_oi ? 1 : s.d_out; p.a_sk = w_oi ? s.r : 1;
+    p.c_sm = k; p.c_sn = 1;
+    p.k_per_split = pl.z_k_per_split;
+    p.c_split_stride = s.r * k;
+    p.sk = make_sketch_params(&od);
+    if (desc->factor_dtype == ACC_BF16) launch_generic<bf16, bf16, float, float, true, true>(p, pl.z_splits, L);
+    else launch_generic<float, float, float, float, true, true>(p, pl.z_splits, L);
+    reduce_to(ACC_F32, (const float*)(ws + pl.off_part), pl.z_splits, s.r * k, z, L);
+  }
+  // Yp [d_in, k] = left . Z
+  {
+    GemmParams p{};
+    p.A = left; p.B = z; p.C = yp;
+    p.M = s.d_in; p.N = k; p.K = s.r;
+    p.a_sm = s.r; p.a_sk = 1; p.b_sk = k; p.b_sn = 1; p.c_sm = k; p.c_sn = 1;
+    p.k_per_split = round_up(s.r, 32);
+    rsvd_gemm(desc->factor_dtype, ACC_F32, ACC_F32, p, 1, L);
+  }
+  // P = orthonormal factor of Yp: Cholesky QR, twice
+  Shape sk = s;
+  sk.r = k;
+  RsvdPlan rp{};
+  rp.g_gram = pl.g_gram; rp.off_gram_part = pl.off_gram_part; rp.off_gram = pl.off_gram; rp.off_rinv = pl.off_rinv;
+  cholesky_qr_pass(sk, rp, ws, s.d_in, s.d_in, yp, q1, nullptr, ACC_F32, nullptr, 0, false, L);
+  cholesky_qr_pass(sk, rp, ws, s.d_in, s.d_in, q1, nullptr, P, desc->factor_dtype, nullptr, 0, false, L);
+  return L.status();
+}
+
+int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* hyper, const void* P, int64_t k,
+                           const void* left, const void* Gr, float* M, float* V, void* W, void* workspace,
+                           size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_lowrank(desc, &s, P ? k : 0, false);
+  if (rc != ACC_OK) return rc;
+  if (!hyper || !left || !Gr || !M || !V || !W) return ACC_ERR_INVALID_ARG;
+  if (hyper->step < 1 || !(hyper->beta1 >= 0.f && hyper->beta1 < 1.f) || !(hyper->beta2 >= 0.f && hyper->beta2 < 1.f) ||
+      !(hyper->eps >= 0.f) || !isfinite(hyper->lr) || !isfinite(hyper->weight_decay) || !isfinite(hyper->scale))
+    return ACC_ERR_INVALID_ARG;
+  if (!aligned16(P) || !aligned16(left) || !aligned16(Gr) || !aligned16(M) || !aligned16(V) || !aligned16(W) ||
+      !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  const LowrankPlan pl = plan_lowrank(desc, s, P ? k : 0);
+  if (!workspace || ws_bytes < pl.step_total) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  char* ws = (char*)workspace;
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  AdamParams h{};
+  h.beta1 = hyper->beta1; h.beta2 = hyper->beta2; h.eps = hyper->eps;
+  h.inv_c1 = (float)(1.0 / (1.0 - pow((double)hyper->beta1, (double)hyper->step)));
+  h.inv_c2 = (float)(1.0 / (1.0 - pow((double)hyper->beta2, (double)hyper->step)));
+  const int64_t kk = P ? k : s.r;            // rows of the moments
+  const int64_t count = kk * s.d_out;
+  const unsigned blocks = (unsigned)ceil_div(count, 1024);
+  void* nrm = ws + pl.off_n;
+  const bool fb = desc->factor_dtype == ACC_BF16;
+  if (!P) {  // the left factor is the projector: the small factor is the projected gradient
+    if (fb) L(adam_factor_kernel<bf16, bf16>, dim3(blocks), dim3(256), (const bf16*)Gr, M, V, (bf16*)nrm, count, h);
+    else L(adam_factor_kernel<float, float>, dim3(blocks), dim3(256), (const float*)Gr, M, V, (float*)nrm, count, h);
+  } else {
+    // T1 [k, r] = P^T . left over the input channels (fp32, channel range split), then the projected gradient
+    // R = T1 . Gr [k, d_out] (or Gr . T1^T [d_out, k]) in fp32
+    float* t1 = (float*)(ws + pl.off_t1);
+    float* proj = (float*)(ws + pl.off_r);
+    {
+      GemmParams p{};
+      p.A = P; p.B = left; p.C = ws + pl.off_part;
+      p.M = k; p.N = s.r; p.K = s.d_in;
+      p.a_sm = 1; p.a_sk = k; p.b_sk = s.r; p.b_sn = 1; p.c_sm = s.r; p.c_sn = 1;
+      p.k_per_split = pl.t1_k_per_split;
+      p.c_split_stride = k * s.r;
+      rsvd_gemm(desc->factor_dtype, desc->factor_dtype, ACC_F32, p, pl.t1_splits, L);
+      reduce_to(ACC_F32, (const float*)(ws + pl.off_part), pl.t1_splits, k * s.r, t1, L);
+    }
+    {
+      GemmParams p{};
+      p.C = proj; p.K = s.r;
+      p.k_per_split = round_up(s.r, 32);
+      if (w_oi) {  // R [d_out, k]: (o, a) = sum_j Gr[o, j] T1[a, j]
+        p.A = Gr; p.B = t1; p.M = s.d_out; p.N = k;
+        p.a_sm = s.r; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.r; p.c_sm = k; p.c_sn = 1;
+        rsvd_gemm(desc->factor_dtype, ACC_F32, ACC_F32, p, 1, L);
+      } else {     // R [k, d_out]
+        p.A = t1; p.B = Gr; p.M = k; p.N = s.d_out;
+        p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
+        rsvd_gemm(ACC_F32, desc->factor_dtype, ACC_F32, p, 1, L);
+      }
+    }
+    if (fb) L(adam_factor_kernel<float, bf16>, dim3(blocks), dim3(256), (const float*)proj, M, V, (bf16*)nrm, count, h);
+    else L(adam_factor_kernel<float, float>, dim3(blocks), dim3(256), (const float*)proj, M, V, (float*)nrm, count, h);
+  }
+  Shape sb = s;
+  sb.r = kk;
+  const FactorProductOut o{W, desc->io_dtype, s.ldw, true, -hyper->lr * hyper->scale,
+                           1.f - hyper->lr * hyper->weight_decay};
+  factor_product(desc, sb, P ? P : left, nrm, o, L);
   return L.status();
 }
 

@@ -37,7 +37,8 @@ struct FastGemmParams {
   int64_t red_stride;     // elements all work-groups of the launch cover per sweep: grid * threads * 4
   int red_G;
   int red_out_bf16;       // 1: red_out is bf16, 0: float
-  int accumulate;         // 1: C += A . B (a bf16 C rounds the product, then the sum), 0: C = A . B
+  int accumulate;         // 0: C = A . B;  1: C = beta C + alpha (A . B) (a bf16 C rounds the product, then the sum)
+  float alpha, beta;      // used when accumulate; 1, 1 is the plain sum
   // Optional split of the K range over work-groups (skinny products whose M x N tiles alone do not fill
   // the chip): tile_blocks == 0 means no split.  Block b works on tile b % tile_blocks and K range
   // [s * k_per_split, min(K, (s + 1) * k_per_split)), s = b / tile_blocks, and stores its partial product
@@ -379,10 +380,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
             const bf16x8 a = __builtin_bit_cast(bf16x8, v), o = __builtin_bit_cast(bf16x8, old);
             bf16x8 sum;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sum[t] = (bf16)((float)a[t] + (float)o[t]);
+            for (int t = 0; t < 8; ++t) sum[t] = (bf16)(p.alpha * (float)a[t] + p.beta * (float)o[t]);
             *dst = __builtin_bit_cast(u32x4, sum);
           } else {
-            *dst = __builtin_bit_cast(u32x4, __builtin_bit_cast(f32x4, v) + __builtin_bit_cast(f32x4, old));
+            *dst = __builtin_bit_cast(u32x4, p.alpha * __builtin_bit_cast(f32x4, v) + p.beta * __builtin_bit_cast(f32x4, old));
           }
         } else {
           *dst = v;

@@ -14,7 +14,8 @@ struct GemmParams {
   int64_t a_sm, a_sk, b_sk, b_sn, c_sm, c_sn;
   int64_t k_per_split;     // K range handled by one blockIdx.z (multiple of 32)
   int64_t c_split_stride;  // elements between the partial results of consecutive splits
-  int accumulate;          // 1: C += A . B (read-modify-write, one rounding), 0: C = A . B
+  int accumulate;          // 0: C = A . B;  1: C = beta C + alpha (A . B) (read-modify-write, one rounding)
+  float alpha, beta;       // used when accumulate; 1, 1 is the plain sum
   SketchParams sk;         // B = S[k = token, n = column] when B_SKETCH
 };
 
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
       const int64_t gm = m0 + wm * 32 + (i >> 2) * 8 + (lane >> 5) * 4 + (i & 3);
       if (gm < p.M) {
         float v = acc[i];
-        if (p.accumulate) v += to_f32(C[gm * p.c_sm + gn * p.c_sn]);
+        if (p.accumulate) v = p.alpha * v + p.beta * to_f32(C[gm * p.c_sm + gn * p.c_sn]);
         C[gm * p.c_sm + gn * p.c_sn] = from_f32<TC>(v);
       }
     }

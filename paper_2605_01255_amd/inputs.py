@@ -149,6 +149,19 @@ def make_dy(lin: Linear) -> np.ndarray:
     return _normal(_rng(lin.data_seed, 3), (lin.n, lin.d_out), 0.01)
 
 
+def make_gradient_factors(lin: Linear, steps: int, factor_dtype: str = None):
+    """Inputs of the optimizer step on the factored gradient, at the magnitudes the layer's own factors have:
+    one left factor [d_in, r] ~ N(0, n / r) (a sketch of unit-variance activations) and, per step t, a small
+    factor [r, d_out] ~ N(0, (0.01 * 0.7^t)^2 * n / r) (gradients that shrink as training goes on).  Stored
+    format of `factor_dtype` (default: the layer's dtype).  Returns (left, [Gr_1, ..., Gr_steps])."""
+    dt = factor_dtype or lin.dtype
+    s = float(np.sqrt(lin.n / lin.r))
+    left = store(_normal(_rng(lin.data_seed, 4), (lin.d_in, lin.r), s), dt)
+    grs = [store(_normal(_rng(lin.data_seed, 100 + t), (lin.r, lin.d_out), 0.01 * 0.7 ** t * s), dt)
+           for t in range(1, steps + 1)]
+    return left, grs
+
+
 def make(lin: Linear):
     """Stored-format inputs: dict with X, W, dY (float32 arrays or uint16 bf16 bit arrays)."""
     return {"X": store(make_x(lin), lin.dtype),
