@@ -130,39 +130,55 @@ class CompressedLinear(torch.nn.Module):
 
 class LowRankAdamW:
     """Update strategy (ii) of Sec. 4 for `CompressedLinear(..., factored_grad=True)` modules: AdamW whose moments
-    have the shape of the small gradient factor [out_features, rank]; the weights are updated in place by
-    acc_lowrank_adamw_step, and no dense gradient or dense optimizer state is ever allocated.  One backward pass
-    per step (factors of several micro-batches cannot be summed).  Biases are left to an ordinary optimizer.
+    have the shape [out_features, proj_rank]; the weights are updated in place by acc_lowrank_adamw_step, and no
+    dense gradient or dense optimizer state is ever allocated.
+
+    proj_rank > 0: moments live in the range of a projector [in_features, proj_rank] computed from the factored
+    gradient by acc_lowrank_projector and refreshed every `proj_gap` steps (the moments are kept across a
+    refresh).  proj_rank = 0: the left factor of each step is its own projector.  One backward pass per step
+    (factors of several micro-batches cannot be summed).  Biases are left to an ordinary optimizer.
     """
 
     def __init__(self, modules, lr: float = 1e-3, betas=(0.9, 0.999), eps: float = 1e-8, weight_decay: float = 0.0,
-                 scale: float = 1.0):
+                 scale: float = 1.0, proj_rank: int = 0, proj_gap: int = 200, seed: int = 0):
         self.modules = [m for m in modules if isinstance(m, CompressedLinear) and m.factored_grad]
         if not self.modules:
             raise ValueError("no CompressedLinear module with factored_grad=True")
         self.lr, self.betas, self.eps, self.weight_decay, self.scale = lr, betas, eps, weight_decay, scale
+        self.proj_rank, self.proj_gap, self.seed = int(proj_rank), int(proj_gap), int(seed)
         self.state = {}
 
     @torch.no_grad()
     def step(self):
-        for m in self.modules:
+        k = self.proj_rank
+        for idx, m in enumerate(self.modules):
             if m.grad_factors is None:
                 continue
             left, gr = m.grad_factors
-            st = self.state.get(m)
-            if st is None:
-                st = self.state[m] = {"step": 0, "exp_avg": torch.zeros(gr.shape, dtype=torch.float32, device=gr.device),
-                                      "exp_avg_sq": torch.zeros(gr.shape, dtype=torch.float32, device=gr.device)}
-            st["step"] += 1
             w = m.weight.data
             if not w.is_contiguous():
                 raise ValueError("weight must be contiguous to be updated in place")
+            st = self.state.get(m)
+            if st is None:
+                rows = k if k else m.rank
+                st = self.state[m] = {
+                    "step": 0,
+                    "exp_avg": torch.zeros(m.out_features, rows, dtype=torch.float32, device=gr.device),
+                    "exp_avg_sq": torch.zeros(m.out_features, rows, dtype=torch.float32, device=gr.device),
+                    "projector": torch.empty(m.in_features, k, dtype=gr.dtype, device=gr.device) if k else None}
+            refresh = k and st["step"] % self.proj_gap == 0
+            st["step"] += 1
+            # a fresh range-finder seed per module and refresh
             desc = acc.make_desc(1, m.in_features, m.out_features, m.rank, io_dtype=_CODES[w.dtype],
-                                 factor_dtype=_CODES[gr.dtype], flags=acc.ACC_FLAG_W_OUT_IN)
+                                 factor_dtype=_CODES[gr.dtype], flags=acc.ACC_FLAG_W_OUT_IN,
+                                 seed=(self.seed << 40) + (idx << 24) + st["step"] // max(self.proj_gap, 1))
+            ws = _workspace(acc.acc_lowrank_workspace_bytes(desc, k), gr.device)
+            if refresh:
+                acc.acc_lowrank_projector(desc, k, left, gr, st["projector"], ws)
             hyper = acc.make_hyper(st["step"], self.lr, self.betas[0], self.betas[1], self.eps, self.weight_decay,
                                    self.scale)
-            ws = _workspace(gr.numel() * gr.element_size(), gr.device)
-            acc.acc_lowrank_adamw_step(desc, hyper, None, 0, left, gr, st["exp_avg"], st["exp_avg_sq"], w, ws)
+            acc.acc_lowrank_adamw_step(desc, hyper, st["projector"], k, left, gr, st["exp_avg"], st["exp_avg_sq"],
+                                       w, ws)
             m.grad_factors = None
 
     def zero_grad(self):

@@ -1029,9 +1029,18 @@ int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* h
       p.k_per_split = pl.t1_k_per_split;
       p.c_split_stride = k * s.r;
       rsvd_gemm(desc->factor_dtype, desc->factor_dtype, ACC_F32, p, pl.t1_splits, L);
-      reduce_to(ACC_F32, (const float*)(ws + pl.off_part), pl.t1_splits, k * s.r, t1, L);
+      L(sum_parts_kernel, dim3((unsigned)ceil_div(k * s.r, 64)), dim3(1024), (const float*)(ws + pl.off_part),
+        pl.t1_splits, k * s.r, t1);
     }
-    {
+    if (fb) {  // projected gradient, moments and normalised step in one launch
+      ProjectAdamParams q{};
+      q.T1 = t1; q.Gr = (const bf16*)Gr; q.M = M; q.V = V; q.N = (bf16*)nrm;
+      q.k = k; q.r = s.r; q.d_out = s.d_out;
+      q.b_sk = w_oi ? 1 : s.d_out; q.b_sn = w_oi ? s.r : 1;
+      q.c_sm = w_oi ? 1 : s.d_out; q.c_sn = w_oi ? k : 1;
+      q.h = h;
+      L(project_adam_kernel, dim3((unsigned)ceil_div(k, 64), (unsigned)ceil_div(s.d_out, 64)), dim3(256), q);
+    } else {
       GemmParams p{};
       p.C = proj; p.K = s.r;
       p.k_per_split = round_up(s.r, 32);
@@ -1044,9 +1053,8 @@ int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* h
         p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = s.d_out; p.c_sn = 1;
         rsvd_gemm(ACC_F32, desc->factor_dtype, ACC_F32, p, 1, L);
       }
+      L(adam_factor_kernel<float, float>, dim3(blocks), dim3(256), (const float*)proj, M, V, (float*)nrm, count, h);
     }
-    if (fb) L(adam_factor_kernel<float, bf16>, dim3(blocks), dim3(256), (const float*)proj, M, V, (bf16*)nrm, count, h);
-    else L(adam_factor_kernel<float, float>, dim3(blocks), dim3(256), (const float*)proj, M, V, (float*)nrm, count, h);
   }
   Shape sb = s;
   sb.r = kk;
