@@ -404,6 +404,7 @@ void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t ch
 // ---- RSVD compressor ------------------------------------------------------------------------
 // Forward chain: Yr = X.Omega -> Cholesky QR twice -> U -> V = X^T.U; every product on the generic MFMA
 // kernel (fp32 matrix instructions wherever an fp32 operand is involved), K-splits reduced by K4.
+constexpr size_t kCholImageBytes = (size_t)(kRsvdMaxRank * kRsvdMaxRank + 2 * kRsvdMaxRank) * 4;  // chol_factor_kernel's output
 struct RsvdPlan {
   bool tuned;   // bf16 inputs and factors, sizes the tuned GEMM kernel takes: skinny products via split K
   int g_gram;   // token splits of the k x k Gram products
@@ -435,7 +436,7 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
     pl.off_q1 = take((size_t)s.n * k * 4);
     pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
     pl.off_gram = take((size_t)k * k * 4);
-    pl.off_rinv = take((size_t)k * k * 4);
+    pl.off_rinv = take(kCholImageBytes);
     if (rsvd_power_iters(d)) {  // Z = X^T.U and its orthonormalised form, [d_in, k] fp32
       pl.off_z0 = take((size_t)s.d_in * k * 4);
       pl.off_z1 = take((size_t)s.d_in * k * 4);
@@ -492,18 +493,26 @@ void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, int64_t m, i
   const int parts = (int)ceil_div(m, rows);
   L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, m, (int)k, rows, gram_part);
   L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, parts, k * k, gram);
-  if (k <= 32) L(chol_inverse_small_kernel<32, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
-  else L(chol_inverse_small_kernel<64, float>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
-  const int64_t kp = round_up(k, 32);
-  const size_t lds = (size_t)(64 * (kp + 1) + kp * (kp % 64 == 0 ? kp + 32 : kp)) * sizeof(float);
+  if (k <= 32) L(chol_factor_kernel<32>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
+  else L(chol_factor_kernel<64>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
   const int64_t rows_out = Ut ? m_pad : m;
   const dim3 grid((unsigned)ceil_div(rows_out, 64));
-  if (qt_dt == ACC_BF16)
-    L.launch_lds(tall_times_small_kernel<bf16>, grid, dim3(256), lds, Yin, m, (int)k, (const float*)rinv, Qf, (bf16*)Qt,
-                 Ut, ldt, rows_out, hilo ? 1 : 0);
-  else
-    L.launch_lds(tall_times_small_kernel<float>, grid, dim3(256), lds, Yin, m, (int)k, (const float*)rinv, Qf,
-                 (float*)Qt, Ut, ldt, rows_out, hilo ? 1 : 0);
+  const int hl = hilo ? 1 : 0;
+  if (k <= 32) {
+    if (qt_dt == ACC_BF16)
+      L(tall_solve_kernel<32, bf16>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
+        (bf16*)Qt, Ut, ldt, rows_out, hl);
+    else
+      L(tall_solve_kernel<32, float>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
+        (float*)Qt, Ut, ldt, rows_out, hl);
+  } else {
+    if (qt_dt == ACC_BF16)
+      L(tall_solve_kernel<64, bf16>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
+        (bf16*)Qt, Ut, ldt, rows_out, hl);
+    else
+      L(tall_solve_kernel<64, float>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
+        (float*)Qt, Ut, ldt, rows_out, hl);
+  }
 }
 
 // out[channels, k] (or its transpose) = A^T . U over the token axis, A [n, lda]; splits reduced by K4.
@@ -676,7 +685,7 @@ LowrankPlan plan_lowrank(const acc_linear_desc* d, const Shape& s, int64_t k) {
     pl.off_q1 = take((size_t)s.d_in * k * 4);
     pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
     pl.off_gram = take((size_t)k * k * 4);
-    pl.off_rinv = take((size_t)k * k * 4);
+    pl.off_rinv = take(kCholImageBytes);
   }
   pl.total = off;
   return pl;

@@ -1,6 +1,7 @@
 // Small dense kernels of the RSVD compressor (Experimental Setup: randomized SVD of Halko et al.): the
-// triangular factor of a k x k Gram matrix and its inverse, the middle step of a Cholesky QR.  The large
-// products around it (X.Omega, Yr^T.Yr, Yr.R^-1, X^T.U, U^T.dY) run on the generic MFMA kernels.
+// triangular factor R of a k x k Gram matrix and Yr.R^-1 by substitution, the middle steps of a Cholesky QR,
+// with the Gram products and the helpers around them.  The large products (X.Omega, X^T.U, U^T.dY) run on the
+// GEMM kernels.
 #pragma once
 #include "acc_common.h"
 #include "acc_rng.h"
@@ -9,74 +10,213 @@ namespace acc {
 
 constexpr int kRsvdMaxRank = 64;   // the k x k factorisation runs on one wave, one matrix row per lane
 
-// G [k, k] (symmetric positive semi-definite, fp32) -> Rinv [k, k] fp32 with G = R^T R, R upper triangular
-// with positive diagonal, Rinv = R^-1 (upper triangular), for k <= K (K = 32 or 64), by ONE wave entirely in
-// registers: lane i holds row i of the symmetric matrix (padded to K with the identity), values move
-// between lanes by v_readlane broadcasts; no LDS, no barriers (the k sequential steps are pure latency, and
-// an LDS version with a barrier per step measured 2-4x slower).
-// A pivot that is not positive beyond rounding (column j of the factored matrix depends on the earlier
-// ones) is dropped: row and column j of Rinv are zero, so the corresponding basis vector comes out as zero
-// and the span of the others is unchanged.
 __device__ __forceinline__ float lane_bcast(float v, int src_lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
 }
-__device__ __forceinline__ double lane_bcast(double v, int src_lane) {
-  const uint64_t u = __builtin_bit_cast(uint64_t, v);
-  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)u, src_lane);
-  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), src_lane);
-  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
-}
 
-template <int K, typename R>
-__global__ __launch_bounds__(64) void chol_inverse_small_kernel(const float* __restrict__ G, float* __restrict__ Rinv,
-                                                                int k) {
+// G [k, k] (symmetric positive semi-definite, fp32) -> the upper triangular factor R of G = R^T R with positive
+// diagonal, for k <= K (K = 32 or 64), by ONE wave: lane i holds row i of the symmetric matrix (padded to K
+// with the identity) in registers; at each step the pivot row goes through LDS to all lanes (same-address reads
+// broadcast; v_readlane broadcasts of the same values measured 20 % slower).  The elimination is done in the
+// square-root-free form (A = L D L^T: one reciprocal per step on the critical path, no square root), eight
+// steps per trip of a rolled loop: after each trip the eight finished rows go to LDS and every lane's registers
+// move down by eight columns, so register indices stay compile-time constants while the loop body stays small.
+// Work done on columns that are already eliminated is harmless: those registers are never read again.  The k
+// steps are a serial chain (LDS round trip, reciprocal, K multiply-adds): 11.9 us at K = 32, 38 us at K = 64.
+// Output, in the form tall_solve_kernel copies to its LDS: Rimg [K * K + 2 K] floats, Rimg[t * K + c] = R[t][c]
+// for t < c < k and zero elsewhere up to index K * K + K, then 1 / R[c][c] for c < k (zero for c >= k).  A pivot
+// that is not positive beyond rounding (column j of the factored matrix depends on the earlier ones) is dropped:
+// its reciprocal is stored as 0 and row j of R is zero, so the corresponding basis vector comes out as zero and
+// the span of the others is unchanged.
+template <int K>
+__global__ __launch_bounds__(64) void chol_factor_kernel(const float* __restrict__ G, float* __restrict__ Rimg,
+                                                         int k) {
+  __shared__ float rows[K][K + 1];
+  __shared__ float scale[K];
   const int lane = threadIdx.x;
-  R a[K], x[K];
+  float a[K];
+  {  // every lane loads from a valid address (clamped), then selects: no branches around the loads
+    const int lr = lane < k ? lane : k - 1;
 #pragma unroll
-  for (int c = 0; c < K; ++c) {
-    a[c] = (lane < k && c < k) ? (R)G[lane * k + c] : (lane == c ? (R)1 : (R)0);
-    x[c] = (R)0;
+    for (int c = 0; c < K; ++c) {
+      const float g = G[lr * k + (c < k ? c : k - 1)];
+      a[c] = (lane < k && c < k) ? g : (lane == c ? 1.f : 0.f);
+    }
   }
-  R diag = (R)0;
+  float diag = 0.f;
 #pragma unroll
   for (int c = 0; c < K; ++c) diag = (c == lane && lane < k) ? a[c] : diag;
-  R maxdiag = (R)0;
+  float maxdiag = 0.f;
 #pragma unroll
   for (int l = 0; l < K; ++l) {
-    const R d = lane_bcast(diag, l);
+    const float d = lane_bcast(diag, l);
     maxdiag = d > maxdiag ? d : maxdiag;
   }
-  const R tol = maxdiag * (R)1e-6;
-  uint64_t dead_mask = 0;
+  const float tol = maxdiag * 1e-6f;
+  float my_piv = 0.f;   // pivot of my row, 0 for a dropped one
+  __shared__ __attribute__((aligned(16))) float bc[2][K];   // the pivot row of a step, for all lanes to read
+#pragma unroll 1
+  for (int jb = 0; jb < K; jb += 8) {
 #pragma unroll
-  for (int j = 0; j < K; ++j) {
-    const R piv = lane_bcast(a[j], j);
-    const bool dead = !(piv > tol);
-    if (dead) dead_mask |= 1ull << j;
-    const R inv_d = dead ? (R)0 : (R)1 / (R)sqrt((double)piv);
-    const R rji = lane > j ? a[j] * inv_d : (R)0;   // R[j][lane] (the matrix is kept symmetric)
+    for (int jj = 0; jj < 8; ++jj) {
+      const int j = jb + jj;
+      // lane j publishes its row (columns j .. of the current register window) through LDS: one wave, so LDS
+      // operations complete in order and no hardware barrier is needed; two buffers alternate so that a step's
+      // writes cannot overtake the previous step's reads
+      float* row = bc[jj & 1];
+      if (lane == j) {
 #pragma unroll
-    for (int c = j + 1; c < K; ++c) {
-      const R rjc = lane_bcast(a[c], j) * inv_d;   // R[j][c]
-      a[c] = lane == j ? rjc : a[c] - rji * rjc;        // lane j keeps row j of R; lanes > j update
+        for (int c = jj & ~3; c < K; c += 4) *(f32x4*)(&row[c]) = f32x4{a[c], a[c + 1], a[c + 2], a[c + 3]};
+      }
+      // other lanes' writes become visible to this lane's reads only across a fence the compiler honours (without
+      // it the reads are hoisted out of the loop as if no one else wrote); at wavefront scope it costs nothing
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      f32x4 rj[K / 4];
+#pragma unroll
+      for (int c = jj & ~3; c < K; c += 4) rj[c / 4] = *(const f32x4*)(&row[c]);
+      const float piv = rj[jj / 4][jj % 4];
+      const bool dead = !(piv > tol);
+      // reciprocal: hardware estimate + one Newton step (about 1 ulp); the elimination needs no more, the
+      // factor's own scaling below uses exact square roots
+      float inv_p = __builtin_amdgcn_rcpf(piv);
+      inv_p = fmaf(fmaf(-piv, inv_p, 1.f), inv_p, inv_p);
+      inv_p = dead ? 0.f : inv_p;
+      my_piv = lane == j ? (dead ? 0.f : piv) : my_piv;
+      const float t = lane > j ? a[jj] * inv_p : 0.f;
+#pragma unroll
+      for (int c = jj + 1; c < K; ++c) a[c] = fmaf(-t, rj[c / 4][c % 4], a[c]);
     }
-    a[j] = lane == j ? (dead ? (R)0 : piv * inv_d) : a[j];
+    if (lane >= jb && lane < jb + 8) {
+#pragma unroll
+      for (int c = 0; c < K; ++c)
+        if (jb + c < K) rows[lane][jb + c] = a[c];
+    }
+#pragma unroll
+    for (int c = 0; c < K - 8; ++c) a[c] = a[c + 8];
+#pragma unroll
+    for (int c = K - 8; c < K; ++c) a[c] = 0.f;
   }
-  // lane i now holds row i of R in a[i..K-1].  Lane c builds column c of the inverse, top row last.
-  const bool dead_c = (dead_mask >> lane) & 1;
+  if (lane < K) scale[lane] = (lane < k && my_piv > 0.f) ? 1.f / sqrtf(my_piv) : 0.f;
+  __syncthreads();
 #pragma unroll
-  for (int i = K - 1; i >= 0; --i) {
-    R sum = lane == i ? (R)1 : (R)0;
-#pragma unroll
-    for (int t = i + 1; t < K; ++t) sum -= lane_bcast(a[t], i) * x[t];
-    const R rii = lane_bcast(a[i], i);
-    const bool dead_i = (dead_mask >> i) & 1;
-    x[i] = (i <= lane && !dead_i && !dead_c) ? sum / rii : (R)0;
+  for (int i = 0; i < (K * K + 2 * K) / 64; ++i) {
+    const int e = lane + 64 * i, t = e / K, c = e % K;
+    float v = 0.f;
+    if (t < K) v = (t < c && c < k) ? rows[t][c] * scale[t] : 0.f;
+    else if (t == K + 1) v = scale[c];
+    Rimg[e] = v;
   }
-  if (lane < k) {
+}
+
+// Q = Y . R^-1 for a tall Y [n, k] fp32 by forward substitution along each row, q_c = (y_c - sum_{t<c} q_t
+// R[t][c]) / R[c][c]: one row per lane, the row in registers, R read from LDS (all lanes read the same address).
+// No explicit inverse is formed.  Columns are taken eight at a time in a rolled loop: substitution inside the
+// block, then the block's contribution is removed from all later columns and the registers move down by eight,
+// so register indices are compile-time constants and the loop body stays small.  Updates that fall on columns
+// past the end touch registers that are never read.
+// Rimg as written by chol_factor_kernel<K>.  Outputs, each optional, rows up to n_rows_out (>= n; rows past n
+// count as zero):
+//   Qf  [n, k] fp32;  Qt [n, k] in TU (the stored factor);  Ut [k, ldt] bf16, the transpose with its
+//   columns n .. n_rows_out - 1 written as zero (K padding of the later products over tokens); with
+//   `hilo` Ut is [2k, ldt]: rows 0 .. k-1 the bf16 rounding of Q^T, rows k .. 2k-1 the bf16 rounding of
+//   the remainder, so that hi + lo carries Q to about 2^-17 relative through a bf16 matrix product.
+// Grid: ceil(n_rows_out / 64) x 64 threads.  k % 8 == 0, k <= K.
+template <int K, typename TU>
+__global__ __launch_bounds__(64) void tall_solve_kernel(const float* __restrict__ Y, int64_t n, int k,
+                                                        const float* __restrict__ Rimg, float* __restrict__ Qf,
+                                                        TU* __restrict__ Qt, bf16* __restrict__ Ut, int64_t ldt,
+                                                        int64_t n_rows_out, int hilo) {
+  // Rs[t * K + c] = R[t][c] for t < c < k, zero elsewhere; one spare row: the update of the last columns reads
+  // up to K - 9 elements past a row's end
+  __shared__ __attribute__((aligned(16))) float Rs[K * K + 2 * K];
+  const float* Ds = Rs + K * K + K;
+  const int tid = threadIdx.x;
+  {
+    constexpr int V4 = (K * K + 2 * K) / 4, PER = (V4 + 63) / 64;
+    f32x4 tmp[PER];
 #pragma unroll
-    for (int i = 0; i < K; ++i)
-      if (i < k) Rinv[i * k + lane] = (float)x[i];
+    for (int i = 0; i < PER; ++i) {
+      const int e = tid + 64 * i;
+      tmp[i] = *(const f32x4*)(Rimg + 4 * (e < V4 ? e : V4 - 1));
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int e = tid + 64 * i;
+      if (e < V4) *(f32x4*)(&Rs[4 * e]) = tmp[i];
+    }
+  }
+  const int64_t row = (int64_t)blockIdx.x * 64 + tid;
+  float y[K];
+#pragma unroll
+  for (int c = 0; c < K; c += 4) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (row < n && c < k) v = *(const f32x4*)(Y + row * k + c);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) y[c + t] = v[t];
+  }
+  __syncthreads();
+#pragma unroll 1
+  for (int cb = 0; cb < k; cb += 8) {
+    float q[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) {
+      float s = y[jj];
+#pragma unroll
+      for (int t = 0; t < jj; ++t) s = fmaf(-q[t], Rs[(cb + t) * K + cb + jj], s);
+      q[jj] = s * Ds[cb + jj];
+    }
+    // four later columns at a time: their eight R entries each are read one group ahead of the multiplies; the
+    // fences keep the compiler from hoisting every read of the trip to its top (450 registers, spills)
+    f32x4 r[8], rn[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) r[jj] = *(const f32x4*)(&Rs[(cb + jj) * K + cb + 8]);
+#pragma unroll
+    for (int c4 = 8; c4 < K; c4 += 4) {
+      if (c4 + 4 < K) {
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) rn[jj] = *(const f32x4*)(&Rs[(cb + jj) * K + cb + c4 + 4]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) y[c4 + u] = fmaf(-q[jj], r[jj][u], y[c4 + u]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) r[jj] = rn[jj];
+    }
+    if (row < n) {
+      if (Qf) {
+        *(f32x4*)(Qf + row * k + cb) = f32x4{q[0], q[1], q[2], q[3]};
+        *(f32x4*)(Qf + row * k + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
+      }
+      if (Qt) {
+        if constexpr (sizeof(TU) == 2) {
+          bf16x8 o;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) o[t] = (bf16)q[t];
+          *(bf16x8*)(Qt + row * k + cb) = o;
+        } else {
+          *(f32x4*)(Qt + row * k + cb) = f32x4{q[0], q[1], q[2], q[3]};
+          *(f32x4*)(Qt + row * k + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
+        }
+      }
+    }
+    if (Ut && row < n_rows_out) {
+#pragma unroll
+      for (int jj = 0; jj < 8; ++jj) {
+        const bf16 hi = row < n ? (bf16)q[jj] : (bf16)0.f;
+        Ut[(int64_t)(cb + jj) * ldt + row] = hi;
+        if (hilo) Ut[(int64_t)(k + cb + jj) * ldt + row] = row < n ? (bf16)(q[jj] - (float)hi) : (bf16)0.f;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < K - 8; ++c) y[c] = y[c + 8];
+#pragma unroll
+    for (int c = K - 8; c < K; ++c) y[c] = 0.f;
   }
 }
 
@@ -169,64 +309,6 @@ __global__ __launch_bounds__(256) void gram_partial_kernel(const float* __restri
       for (int e = 0; e < 16; ++e) {
         const int row = i0 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
         if (row < k && col < k) out[row * k + col] = acc[q][e];
-      }
-    }
-  }
-}
-
-// Q = Y . Rinv for a tall Y [n, k] fp32 and a k x k fp32 Rinv, fp32 matrix instructions.  One work-group
-// per 64 rows, rows up to n_rows_out (>= n; rows past n count as zero).  Outputs, each optional:
-//   Qf  [n, k] fp32;  Qt [n, k] in TU (the stored factor);  Ut [k, ldt] bf16, the transpose with its
-//   columns n .. n_rows_out - 1 written as zero (K padding of the later products over tokens); with
-//   `hilo` Ut is [2k, ldt]: rows 0 .. k-1 the bf16 rounding of Q^T, rows k .. 2k-1 the bf16 rounding of
-//   the remainder, so that hi + lo carries Q to about 2^-17 relative through a bf16 matrix product.
-template <typename TU>
-__global__ __launch_bounds__(256) void tall_times_small_kernel(const float* __restrict__ Y, int64_t n, int k,
-                                                               const float* __restrict__ Rinv,
-                                                               float* __restrict__ Qf, TU* __restrict__ Qt,
-                                                               bf16* __restrict__ Ut, int64_t ldt,
-                                                               int64_t n_rows_out, int hilo) {
-  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kp = (k + 31) / 32 * 32, nb = kp / 32;
-  const int ldy = kp + 1, ldr = (kp % 64 == 0) ? kp + 32 : kp;
-  float* Ys = (float*)smem_raw;           // [64][ldy]
-  float* Rs = Ys + 64 * ldy;              // [kp][ldr]
-  const int64_t r0 = (int64_t)blockIdx.x * 64;
-  for (int e = tid; e < 64 * kp; e += 256) {
-    const int r = e / kp, c = e % kp;
-    Ys[r * ldy + c] = (r0 + r < n && c < k) ? Y[(r0 + r) * k + c] : 0.f;
-  }
-  for (int e = tid; e < kp * kp; e += 256) {
-    const int r = e / kp, c = e % kp;
-    Rs[r * ldr + c] = (r < k && c < k) ? Rinv[r * k + c] : 0.f;
-  }
-  __syncthreads();
-  // 2 x nb output blocks of 32 x 32 over 4 waves
-  for (int blk = wave; blk < 2 * nb; blk += 4) {
-    const int m0 = (blk / nb) * 32, c0 = (blk % nb) * 32;
-    f32x16 acc;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-    for (int kk = 0; kk < kp; kk += 2) {
-      const float a = Ys[(m0 + (lane & 31)) * ldy + kk + (lane >> 5)];
-      const float b = Rs[(kk + (lane >> 5)) * ldr + c0 + (lane & 31)];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
-    }
-    const int col = c0 + (lane & 31);
-    if (col < k) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int64_t row = r0 + m0 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3);
-        if (row < n) {
-          if (Qf) Qf[row * k + col] = acc[e];
-          if (Qt) Qt[row * k + col] = from_f32<TU>(acc[e]);
-        }
-        if (Ut && row < n_rows_out) {
-          const bf16 hi = row < n ? (bf16)acc[e] : (bf16)0.f;
-          Ut[(int64_t)col * ldt + row] = hi;
-          if (hilo) Ut[(int64_t)(k + col) * ldt + row] = row < n ? (bf16)(acc[e] - (float)hi) : (bf16)0.f;
-        }
       }
     }
   }
