@@ -165,3 +165,56 @@ def test_flag_constants_match_the_header():
     shift = int(re.search(r"#define ACC_FLAG_RSVD_POWER_SHIFT (\d+)", text).group(1))
     assert acc.ACC_FLAG_RSVD_POWER_SHIFT == shift == 8
     assert re.search(r"ACC_F32 = 0, ACC_BF16 = 1", text) and (acc.ACC_F32, acc.ACC_BF16) == (0, 1)
+
+
+def test_lowrank_optimizer_entry_points_validate_their_arguments():
+    d = acc.make_desc(n=256, d_in=256, d_out=512, r=64)
+    h = acc.make_hyper(1, 1e-3)
+    step, proj = acc._lib.acc_lowrank_adamw_step, acc._lib.acc_lowrank_projector
+    big = 1 << 40
+    ptrs = (0x1000, 0x2000, 0x3000, 0x4000, 0x6000)   # left, Gr, M, V, W
+
+    def call_step(desc=d, hyper=h, P=0x7000, k=16, ws=0x5000, ws_bytes=big, ptrs=ptrs):
+        return step(ctypes.byref(desc) if desc is not None else None, ctypes.byref(hyper) if hyper is not None else None,
+                    P, k, *ptrs, ws, ws_bytes, None)
+
+    assert call_step() in (0, -6)
+    assert call_step(P=None, k=0) in (0, -6)
+    assert call_step(desc=None) == -1 and call_step(hyper=None) == -1
+    for i in range(5):
+        bad = list(ptrs); bad[i] = None
+        assert call_step(ptrs=tuple(bad)) == -1, i
+    assert call_step(P=0x7004) == -3 and call_step(ws=0x5008) == -3
+    for k in (12, 264, -8):
+        assert call_step(k=k) == -2, k
+    assert call_step(P=None, k=12) in (0, -6)           # k is ignored without a projector
+    need = acc.acc_lowrank_workspace_bytes(d, 16)
+    assert need > 0 and acc.acc_lowrank_workspace_bytes(d, 0) == 512 * 64 * 2
+    assert call_step(ws=None) == -5
+    assert call_step(P=None, k=0, ws_bytes=512 * 64 * 2 - 1) == -5
+    for kw in (dict(step=0), dict(beta1=1.0), dict(beta2=1.5), dict(eps=-1e-8), dict(lr=float("inf")),
+               dict(weight_decay=float("nan")), dict(scale=float("inf"))):
+        assert call_step(hyper=acc.make_hyper(**{**dict(step=1, lr=1e-3), **kw})) == -1, kw
+    for flag in (acc.ACC_FLAG_SKIP_SKETCH, acc.ACC_FLAG_ONE_LAUNCH, acc.ACC_FLAG_DW_ACCUMULATE):
+        assert call_step(desc=acc.make_desc(n=256, d_in=256, d_out=512, r=64, flags=flag)) == -1
+    assert call_step(desc=acc.make_desc(n=256, d_in=256, d_out=512, r=64, flags=acc.ACC_FLAG_W_OUT_IN)) in (0, -6)
+
+    def call_proj(k=16, left=0x1000, Gr=0x2000, P=0x7000, ws=0x5000, ws_bytes=big):
+        return proj(ctypes.byref(d), k, left, Gr, P, ws, ws_bytes, None)
+
+    assert call_proj() in (0, -6)
+    assert call_proj(left=None) == -1 and call_proj(Gr=None) == -1 and call_proj(P=None) == -1
+    for k in (0, 4, 72, 128):      # below 8, not a multiple of 8, above r = 64 / the rank limit
+        assert call_proj(k=k) == -2, k
+    assert call_proj(ws_bytes=need - 1) == -5 and call_proj(P=0x7002) == -3
+    assert ctypes.sizeof(acc.AccAdamwHyper) == 32
+
+
+def test_hyperparameter_struct_matches_header():
+    text = open(HEADER).read()
+    body = re.search(r"typedef struct acc_adamw_hyper \{(.*?)\} acc_adamw_hyper;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = []
+    for typ, names in re.findall(r"\b(float|int32_t)\s+([\w\s,]+);", body):
+        fields += [(n.strip(), ctypes.c_float if typ == "float" else ctypes.c_int32) for n in names.split(",")]
+    assert fields == list(acc.AccAdamwHyper._fields_)

@@ -86,3 +86,31 @@ def test_operands_beyond_two_gib_sampled(acc):
     lin = inputs.Linear("big_x", 140003, 8192, 1024, 128, x_kind="plain")
     assert lin.n * lin.d_in * 2 > 2 ** 31
     _sampled_check(acc, lin, np.random.default_rng(4))
+
+
+def test_c5_q_rsvd_rank32_sampled(acc):
+    """RSVD compressor at the 8B-shaped q projection (n = 65536, 4096 -> 4096) and the paper's rank 32: the
+    factors U, V, Gr and dW whole (their oracle products are thin), the exact products Y and dX on sampled rows."""
+    import dataclasses
+    import torch
+    lin = dataclasses.replace([l for l in inputs.config("c5") if l.name == "c5.q"][0], r=32)
+    data = inputs.make(lin)
+    dev = "cuda:0"
+    X, W, dY = (acc.to_device(data[k], dev) for k in ("X", "W", "dY"))
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed)
+    bf = torch.bfloat16
+    Y = torch.empty(lin.n, lin.d_out, dtype=bf, device=dev); dX = torch.empty(lin.n, lin.d_in, dtype=bf, device=dev)
+    U = torch.empty(lin.n, lin.r, dtype=bf, device=dev); V = torch.empty(lin.d_in, lin.r, dtype=bf, device=dev)
+    Gr = torch.empty(lin.r, lin.d_out, dtype=bf, device=dev); dW = torch.empty(lin.d_in, lin.d_out, dtype=bf, device=dev)
+    acc.acc_linear_fwd_rsvd(desc, X, W, Y, U, V, acc.alloc_workspace(desc, False, dev, rsvd=True))
+    acc.acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, dW, acc.alloc_workspace(desc, True, dev, rsvd=True))
+    torch.cuda.synchronize()
+    Xo, Wo, dYo = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
+    Uo, Vo = orc.rsvd_factors(Xo, lin.seed, lin.r)
+    Gro = Uo.T @ dYo
+    rows = np.sort(np.random.default_rng(5).choice(lin.n, size=256, replace=False))
+    errs = {"U": gu.rel(acc.to_host_f64(U), Uo), "V": gu.rel(acc.to_host_f64(V), Vo),
+            "Gr": gu.rel(acc.to_host_f64(Gr), Gro), "dW": gu.rel(acc.to_host_f64(dW), Vo @ Gro),
+            "Y": gu.rel(acc.to_host_f64(Y[rows]), Xo[rows] @ Wo), "dX": gu.rel(acc.to_host_f64(dX[rows]), dYo[rows] @ Wo.T)}
+    print(lin.name, "rsvd k=32", " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
+    assert all(v <= 1e-2 for v in errs.values()), errs

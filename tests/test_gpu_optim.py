@@ -204,6 +204,13 @@ def test_c2_shape_one_step_sampled(acc):
     check(got, want, 1e-2, 1e-2, "c2")
 
 
+def test_c5_gate_shape_projected_step(acc):
+    """The 8B-shaped gate projection (4096 x 14336, r = 512) through a rank-64 projector, one step, whole outputs."""
+    lin = [l for l in inputs.config("c5") if l.name == "c5.gate"][0]
+    got, want = run_steps(acc, lin, 1, {**HYPER, "lr": 0.2}, k=64)
+    check(got, want, 1e-2, 1e-2, "c5.gate k=64")
+
+
 def test_invalid_hyperparameters_are_refused(acc):
     import torch
     lin = inputs.Linear("opt.bad", 256, 64, 64, 8, dtype="f32", x_kind="plain")
@@ -229,3 +236,58 @@ def test_invalid_hyperparameters_are_refused(acc):
     assert acc.acc_lowrank_workspace_bytes(desc, 12) == 0
     torch.cuda.synchronize()
     assert float(z.abs().sum()) == 0.0
+
+
+def test_rsvd_pass_and_optimizer_step_replay_from_a_hip_graph(acc):
+    """A whole training step of update strategy (ii) with the RSVD compressor (forward, backward with the gradient
+    left factored, projector refresh, optimizer step) captured once and replayed: the calls only enqueue kernels.
+    Every replay starts from the same weight and moments (restored by eager copies between replays) and must
+    reproduce the eager result bit for bit."""
+    import torch
+    dev = "cuda:0"
+    lin = inputs.Linear("graph.opt", 2100, 1024, 1544, 32, dtype="bf16")
+    data = inputs.make(lin)
+    X, W0, dY = (acc.to_device(data[k], dev) for k in ("X", "W", "dY"))
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=7)
+    k = 16
+    bf = torch.bfloat16
+    W = W0.clone()
+    Y = torch.empty(lin.n, lin.d_out, dtype=bf, device=dev); dX = torch.empty(lin.n, lin.d_in, dtype=bf, device=dev)
+    U = torch.empty(lin.n, lin.r, dtype=bf, device=dev); V = torch.empty(lin.d_in, lin.r, dtype=bf, device=dev)
+    Gr = torch.empty(lin.r, lin.d_out, dtype=bf, device=dev); P = torch.empty(lin.d_in, k, dtype=bf, device=dev)
+    M = torch.zeros(k, lin.d_out, device=dev); Vm = torch.zeros(k, lin.d_out, device=dev)
+    ws_f = acc.alloc_workspace(desc, False, dev, rsvd=True)
+    ws_b = acc.alloc_workspace(desc, True, dev, rsvd=True)
+    ws_o = acc.alloc_lowrank_workspace(desc, k, dev)
+    hyper = acc.make_hyper(1, lr=0.05, weight_decay=0.01)
+
+    def enqueue():
+        acc.acc_linear_fwd_rsvd(desc, X, W, Y, U, V, ws_f)
+        acc.acc_linear_bwd_rsvd(desc, dY, W, U, V, dX, Gr, None, ws_b)
+        acc.acc_lowrank_projector(desc, k, V, Gr, P, ws_o)
+        acc.acc_lowrank_adamw_step(desc, hyper, P, k, V, Gr, M, Vm, W, ws_o)
+
+    def reset():
+        W.copy_(W0); M.zero_(); Vm.zero_()
+
+    enqueue()
+    torch.cuda.synchronize()
+    eager = {n_: t.clone() for n_, t in (("W", W), ("M", M), ("V", Vm), ("P", P), ("Y", Y), ("dX", dX))}
+    assert not torch.equal(W, W0)
+    reset()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        reset()
+        for t in (P, Y, dX):
+            t.fill_(3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n_, t in (("W", W), ("M", M), ("V", Vm), ("P", P), ("Y", Y), ("dX", dX)):
+            assert torch.equal(t, eager[n_]), (rep, n_)
