@@ -5,6 +5,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <tuple>
 #include <utility>
 
@@ -61,7 +63,7 @@ int hip_fail(hipError_t e, const char* what) {
 
 // The library only runs on gfx950; the answer is cached per device ordinal.
 int check_device() {
-  static int cached[64];  // 0 unknown, 1 ok, -1 not gfx950
+  static std::atomic<int> cached[64];  // 0 unknown, 1 ok, -1 not gfx950
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
@@ -77,22 +79,24 @@ int check_device() {
 }
 
 // Kernels whose dynamic-LDS limit has been raised on a device (the attribute sticks to the function, so
-// it is set once per kernel and device, not per launch).  A benign race only sets it twice.
+// it is set once per kernel and device, not per launch).  The table is shared by all host threads.
 struct RaisedEntry { const void* kernel; int device; };
 RaisedEntry g_raised[64];
 int g_raised_count = 0;
+std::mutex g_raised_mutex;
 bool lds_limit_raised(const void* kernel) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return false;
-  for (int i = 0; i < g_raised_count && i < 64; ++i)
+  std::lock_guard<std::mutex> lock(g_raised_mutex);
+  for (int i = 0; i < g_raised_count; ++i)
     if (g_raised[i].kernel == kernel && g_raised[i].device == dev) return true;
   return false;
 }
 void lds_limit_note(const void* kernel) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return;
-  const int i = g_raised_count;
-  if (i < 64) { g_raised[i] = RaisedEntry{kernel, dev}; g_raised_count = i + 1; }
+  std::lock_guard<std::mutex> lock(g_raised_mutex);
+  if (g_raised_count < 64) g_raised[g_raised_count++] = RaisedEntry{kernel, dev};
 }
 
 // Enqueues kernels on one stream and remembers the first launch error.
