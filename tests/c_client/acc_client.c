@@ -89,6 +89,39 @@ int main(void) {
       const double e = fabs(s - hdW[c * d_out + o]);
       if (e > worst) worst = e;
     }
+  /* optimizer update from the factors, left factor as projector, first step from zero moments with eps = 0:
+     the normalised step is sign(Gr), so W moves by -lr * Xs . sign(Gr) (checked here with plain loops) */
+  {
+    float *M, *V;
+    void* wso;
+    const size_t ws_o = acc_lowrank_workspace_bytes(&d, 0);
+    if (ws_o == 0) { fprintf(stderr, "optimizer descriptor refused\n"); return 1; }
+    CHECK_HIP(hipMalloc((void**)&M, sizeof(float) * r * d_out));
+    CHECK_HIP(hipMalloc((void**)&V, sizeof(float) * r * d_out));
+    CHECK_HIP(hipMalloc(&wso, ws_o));
+    CHECK_HIP(hipMemset(M, 0, sizeof(float) * r * d_out));
+    CHECK_HIP(hipMemset(V, 0, sizeof(float) * r * d_out));
+    acc_adamw_hyper h;
+    h.lr = 0.01f; h.beta1 = 0.9f; h.beta2 = 0.999f; h.eps = 0.0f; h.weight_decay = 0.0f; h.scale = 1.0f;
+    h.step = 1; h.reserved = 0;
+    rc = acc_lowrank_adamw_step(&d, &h, NULL, 0, Xs, Gr, M, V, W, wso, ws_o, NULL);
+    if (rc != ACC_OK) { fprintf(stderr, "acc_lowrank_adamw_step: %s\n", acc_status_string(rc)); return 1; }
+    CHECK_HIP(hipDeviceSynchronize());
+    float* hW1 = malloc(sizeof(float) * d_in * d_out);
+    CHECK_HIP(hipMemcpy(hW1, W, sizeof(float) * d_in * d_out, hipMemcpyDeviceToHost));
+    for (int c = 0; c < d_in; ++c)
+      for (int o = 0; o < d_out; ++o) {
+        double s = 0.0;
+        for (int j = 0; j < r; ++j) {
+          const float g = hGr[j * d_out + o];
+          s += (double)hXs[c * r + j] * (g > 0.f ? 1.0 : (g < 0.f ? -1.0 : 0.0));
+        }
+        const double e = fabs((double)hW[c * d_out + o] - 0.01 * s - hW1[c * d_out + o]);
+        if (e > worst) worst = e;
+      }
+    h.step = 0;
+    if (acc_lowrank_adamw_step(&d, &h, NULL, 0, Xs, Gr, M, V, W, wso, ws_o, NULL) != ACC_ERR_INVALID_ARG) return 1;
+  }
   /* a refused call must come back as an error code, not a crash */
   d.r = 20;
   const int refused = acc_linear_fwd(&d, X, W, Y, Xs, ws, ws_f, NULL);
