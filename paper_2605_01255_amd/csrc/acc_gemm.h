@@ -250,12 +250,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   };
 
   // One k-step with a fixed instruction order: MFMA q of the step carries (at most) one operand read
-  // for the next step and, every G_EVERY MFMAs, one global->LDS wave-load of the next tile.  Fences
+  // for the next step and, every G_EVERY MFMAs, one global->LDS wave-load of a later tile.  Fences
   // keep the compiler from clustering the memory instructions, which stalls the wave in VMEM issue
   // while the texture path drains and starves the MFMA pipe.
   constexpr int NM = TM * TN;
   constexpr int NG_TOTAL = A_LOADS + B_LOADS;
-  constexpr int G_STEPS = 3;                                   // k-steps that carry wave-loads
+  // The transfers of a tile are spread over the first two k-steps after the barrier that releases their
+  // stage (the last k-step of one loop trip and the first of the next): they then have two to three
+  // k-steps to land before the next barrier.  Spread over the three k-steps that end at that barrier, as
+  // before, the last third had under one k-step (-1.9 % on a step, -8 % on a GEMM whose input comes from
+  // HBM); all in one k-step, one per MFMA, stalls VMEM issue (+1 % step time).
+  constexpr int G_STEPS = 2;                                   // k-steps that carry wave-loads
   constexpr int G_PER_STEP = (NG_TOTAL + G_STEPS - 1) / G_STEPS;
   constexpr int G_EVERY = NM / G_PER_STEP > 0 ? NM / G_PER_STEP : 1;
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s,
@@ -313,24 +318,32 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   for (int i = 0; i < TM; ++i) read_a1(smem, 0, i, af[0]);
 #pragma unroll
   for (int j = 0; j < TN; ++j) read_b1(smem, 0, j, bfr[0]);
+  if (KT > 1) {  // first half of tile 1 (the loop's last k-step does this for the tiles after it)
+#pragma unroll
+    for (int g = 0; g < G_PER_STEP; ++g)
+      if (g < NG_TOTAL) issue_one(g, 1, smem_lds + STAGE);
+  }
 
   for (int kt = 0; kt < KT; ++kt) {
     const char* cur = smem + (kt & 1) * STAGE;
     const char* nxt = smem + ((kt + 1) & 1) * STAGE;
     const uint32_t nxt_lds = smem_lds + ((kt + 1) & 1) * STAGE;
-    // Branch-free body: the last iteration re-loads its own tile into the idle stage, unused.
+    // Branch-free first k-step: the last iteration re-loads half of its own tile into the idle stage, unused
+    // (and waited for at the barrier below).
     const int kt_next = kt + 1 < KT ? kt + 1 : kt;
     __builtin_amdgcn_sched_barrier(0);
-    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], 0 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 1 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 2 * G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);
+    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt_next, nxt_lds);  // second half of tile kt + 1
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 0, 0, kt_next, nxt_lds);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 0, 0, kt_next, nxt_lds);
     // The next tile must have landed (every wave's transfers) before anyone reads it, and every
     // wave must be done reading `cur` before the tile after next is written over it.
     wait_vmcnt0();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    // last k-step of this tile covers the latency of the first operand reads of the next one
-    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, 0, kt_next, nxt_lds);
+    // last k-step of this tile covers the latency of the first operand reads of the next one and carries the
+    // first half of the transfers of the tile after next into the stage the barrier has just released (none
+    // past the last tile: nothing may be in flight when the epilogue reuses the LDS)
+    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, kt + 2 < KT ? G_PER_STEP : 0, kt + 2, smem_lds + (kt & 1) * STAGE);
   }
 
   // ---- epilogue ----
