@@ -96,7 +96,9 @@ __device__ __forceinline__ u32x4 make_rsrc(const void* base, int64_t bytes) {
 // read of the destination stage.
 __device__ __forceinline__ void buffer_to_lds_b128(u32x4 rsrc, uint32_t voffset, uint32_t soffset,
                                                    uint32_t lds_wave_base) {
-  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds"
+  // s_nop: one wait state between the scalar write of M0 (placed by the compiler right before this block) and
+  // the transfer that reads it, as the ISA asks for
+  asm volatile("s_nop 0\n\tbuffer_load_dwordx4 %0, %1, %2 offen lds"
                :
                : "v"(voffset), "s"(rsrc), "s"(soffset), "{m0}"(lds_wave_base)  // M0 = LDS destination
                : "memory");
