@@ -275,9 +275,13 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cb[j], ca[i], acc[i][j], 0, 0, 0);
       if constexpr (NM >= 2 * (TM + TN)) {  // enough MFMAs: one read on every second one (+0.4 % on a step
                                             // against eight reads on the first eight MFMAs of sixteen)
+        // in the order the next k-step consumes them (its MFMA i * TN + j needs a[i] and b[j]): a0, every b,
+        // then the other a: each read is then at least ten MFMAs ahead of its use
         if (q % 2 == 0) {
-          if (q / 2 < TM) read_a1(rd_stage, rd_s, q / 2, na);
-          else if (q / 2 < TM + TN) read_b1(rd_stage, rd_s, q / 2 - TM, nb);
+          const int r = q / 2;
+          if (r == 0) read_a1(rd_stage, rd_s, 0, na);
+          else if (r <= TN) read_b1(rd_stage, rd_s, r - 1, nb);
+          else if (r < TM + TN) read_a1(rd_stage, rd_s, r - TN, na);
         }
       } else if constexpr (NM >= TM + TN) {
         if (q < TM) read_a1(rd_stage, rd_s, q, na);
