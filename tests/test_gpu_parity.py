@@ -309,3 +309,59 @@ def test_all_zero_inputs_give_exact_zeros(acc):
     got = gu.run_layer(acc, lin, zg, want_db=True)
     for key in ("dX", "Gr", "dW", "dB"):
         assert np.all(got[key] == 0.0), key
+
+
+def test_concurrent_host_threads_on_their_own_streams(acc):
+    """The library keeps no state between calls: two host threads, each with its own stream, buffers and workspace,
+    call it at the same time (ctypes releases the interpreter lock during a call) and must reproduce, bit for bit,
+    what the same calls give one after the other."""
+    import threading
+    import torch
+    dev = "cuda:0"
+    lins = [inputs.Linear("thr0", 2100, 1024, 1544, 128, dtype="bf16", seed=11),
+            inputs.Linear("thr1", 1800, 1544, 1024, 64, dtype="bf16", seed=12)]
+    jobs = []
+    for lin in lins:
+        data = inputs.make(lin)
+        X, W, dY = (acc.to_device(data[k], dev) for k in ("X", "W", "dY"))
+        desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed)
+        bf = torch.bfloat16
+        outs = {k: torch.empty(*shp, dtype=bf, device=dev) for k, shp in
+                (("Y", (lin.n, lin.d_out)), ("dX", (lin.n, lin.d_in)), ("Xs", (lin.d_in, lin.r)),
+                 ("Gr", (lin.r, lin.d_out)), ("dW", (lin.d_in, lin.d_out)))}
+        jobs.append(dict(desc=desc, X=X, W=W, dY=dY, outs=outs, ws_f=acc.alloc_workspace(desc, False, dev),
+                         ws_b=acc.alloc_workspace(desc, True, dev), stream=torch.cuda.Stream()))
+
+    def run(job, reps):
+        for _ in range(reps):
+            o = job["outs"]
+            acc.acc_linear_fwd(job["desc"], job["X"], job["W"], o["Y"], o["Xs"], job["ws_f"], stream=job["stream"])
+            acc.acc_linear_bwd(job["desc"], job["dY"], job["W"], o["Xs"], o["dX"], o["Gr"], o["dW"], job["ws_b"],
+                               stream=job["stream"])
+
+    for job in jobs:            # serial reference
+        run(job, 1)
+    torch.cuda.synchronize()
+    ref = [{k: v.clone() for k, v in job["outs"].items()} for job in jobs]
+    for job in jobs:
+        for v in job["outs"].values():
+            v.fill_(3.0)
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(job):
+        try:
+            run(job, 20)
+        except Exception as e:   # surfaces in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(job,)) for job in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for job, r in zip(jobs, ref):
+        for k in r:
+            assert torch.equal(job["outs"][k], r[k]), k
