@@ -340,7 +340,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       if (g < NG_TOTAL) issue_one(g, 1, smem_lds + STAGE);
   }
 
-  for (int kt = 0; kt < KT; ++kt) {
+  // One K tile.  `ahead` (a compile-time constant at each call below): the tile after next exists, so the last
+  // k-step carries the first half of its transfers; the two last K tiles of the range are a second copy of the
+  // body without them, which keeps eight uniform branches per K tile out of the steady-state loop.
+  auto ktile = [&](int kt, auto ahead) {
     const char* cur = smem + (kt & 1) * STAGE;
     const char* nxt = smem + ((kt + 1) & 1) * STAGE;
     const uint32_t nxt_lds = smem_lds + ((kt + 1) & 1) * STAGE;
@@ -359,8 +362,12 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
     // last k-step of this tile covers the latency of the first operand reads of the next one and carries the
     // first half of the transfers of the tile after next into the stage the barrier has just released (none
     // past the last tile: nothing may be in flight when the epilogue reuses the LDS)
-    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, kt + 2 < KT ? G_PER_STEP : 0, kt + 2, smem_lds + (kt & 1) * STAGE);
-  }
+    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, decltype(ahead)::value ? G_PER_STEP : 0, kt + 2,
+          smem_lds + (kt & 1) * STAGE);
+  };
+  int kt = 0;
+  for (; kt + 2 < KT; ++kt) ktile(kt, std::true_type{});
+  for (; kt < KT; ++kt) ktile(kt, std::false_type{});
 
   // ---- epilogue ----
   // Lane holds output row (lane & 31) of each 32 x 32 block and columns 8 * (e / 4) + 4 * (lane >> 5) +
