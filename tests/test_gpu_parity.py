@@ -155,6 +155,15 @@ def test_bf16_tuned_kernel_shapes(acc, n, d_in, d_out, r):
     _check(acc, inputs.Linear(f"fast_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16"))
 
 
+@pytest.mark.parametrize("d_in,d_out,r", [(64, 3080, 64), (128, 4104, 128), (192, 3080, 192), (256, 3080, 64),
+                                          (320, 3080, 64)])
+def test_tuned_gemm_with_one_to_five_k_tiles(acc, d_in, d_out, r):
+    """Short contractions through the 256 x 256 tile (n and d_out large enough for it): one to five K tiles, so
+    every combination of the steady-state loop and its two closing K tiles is taken (forward K = d_in, dense
+    gradient K = r, backward K = d_out long)."""
+    _check(acc, inputs.Linear(f"ktiles_{d_in}x{d_out}_r{r}", 4100, d_in, d_out, r, dtype="bf16"))
+
+
 def test_tuned_kernels_fp32_dw_and_strides(acc):
     lin = inputs.Linear("fast_strided", 1500, 512, 768, 128, dtype="bf16")
     _check(acc, lin, dw_dtype=0, pad=(64, 8, 72), row_offset=4 * 77, seed=0xABCDEF0123)
