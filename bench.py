@@ -24,8 +24,8 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=200)  # the clocks settle over about 0.1 s of load
     ap.add_argument("--config", default="c2", help="c1 | c2 | c3_r256 | c4 | c5 (a named linear: c4.k)")
     ap.add_argument("--layer", default=None, help="c4 | c5: time all linears of a decoder layer instead (own JSON line)")
     ap.add_argument("--no-dw", action="store_true", help="leave the dense dW out of the step")
