@@ -28,7 +28,11 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 __device__ __forceinline__ float uniform_from_word(uint32_t x) {
-  return ((float)(x >> 9) + 0.5f) * 0x1p-23f;  // every step exact in fp32
+  // ((x >> 9) + 0.5) 2^-23 in two instructions, both exact: v_alignbit_b32 puts the 23 bits under the exponent of
+  // 1.0 (a = 1 + (x >> 9) 2^-23), and a - (1 - 2^-24) = (2 (x >> 9) + 1) 2^-24 is representable, so the
+  // subtraction does not round.  (Shift, convert, add, multiply take four.)
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_alignbit(0x7Fu, x, 9u));
+  return a - 0x1.fffffep-1f;
 }
 
 // a ^ b ^ k in one instruction (v_bitop3_b32 with truth table 0x96 = three-input xor; k wave-uniform).
