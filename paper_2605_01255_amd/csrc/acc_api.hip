@@ -314,15 +314,20 @@ SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, in
     sp.G = generic_sketch_splits(n, channels, d->r);
     return sp;
   }
-  if (d->r % 128 == 0) { sp.ch = 512; sp.rc = 128; }
-  else if (d->r <= 32) { sp.ch = 1024; sp.rc = 32; }  // small ranks (the paper's 8 and 32): half the generated columns
-  else { sp.ch = 1024; sp.rc = 64; }
+  // 8-wave tiles of 512 channels, one work-group per compute unit.  64 sketch columns (64 accumulators per
+  // lane) by default: half the partial bytes of the 128-column tile for the same generator and matrix work.
+  // The 128-column tile stays where eight or more column slices would re-read a long token range from L2
+  // (measured: r = 512 at 65536 tokens), and in the one-launch kernel, which interleaves it with GEMM tiles;
+  // the choice must be the same in every call that sees this descriptor (workspace size, forward, backward).
+  sp.ch = 512;
+  const bool wide = d->r % 128 == 0 && ((d->flags & ACC_FLAG_ONE_LAUNCH) || (d->r > 256 && n > 32768));
+  sp.rc = wide ? 128 : 64;
   sp.n_cslab = (int)ceil_div(channels, sp.ch);
   sp.n_js = (int)ceil_div(d->r, sp.rc);  // the last column slice may be partly empty (rank % 64 != 0)
-  int64_t G = (256 + sp.n_cslab * sp.n_js / 2) / (sp.n_cslab * sp.n_js);
+  int64_t G = 256 / (sp.n_cslab * sp.n_js);  // never more work-groups than compute units
   const int64_t max_by_tokens = ceil_div(n, 256);
   if (G > max_by_tokens) G = max_by_tokens;
-  if (G > (sp.rc == 32 ? 64 : 32)) G = sp.rc == 32 ? 64 : 32;  // few, narrow tiles: more token splits fill the chip
+  if (G > 64) G = 64;
   if (G < 1) G = 1;
   sp.tokens_per_split = (int)round_up(ceil_div(n, G), 32);
   sp.G = (int)ceil_div(n, sp.tokens_per_split);
@@ -348,17 +353,12 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
   p.sk = make_sketch_params(d);
   const int pairs = sp.n_cslab * sp.G;
   const dim3 grid((unsigned)(8 * sp.n_js * ceil_div(pairs, 8)));
-  if (sp.rc == 128) {  // 512 x 128 tile, 8 waves: two waves per SIMD overlap MFMA and Philox (-17 % vs 4 waves)
-    if (transposed) L.launch_lds(sketch8_kernel<true>, grid, dim3(512), (size_t)128 * 1024, p);
-    else L.launch_lds(sketch8_kernel<false>, grid, dim3(512), (size_t)128 * 1024, p);
-  } else if (sp.rc == 32) {  // 1024 x 32 tile, 4 waves along the channels
-    const size_t lds = sketch_bf16_lds_bytes<4, 1, 8>();
-    if (transposed) L.launch_lds(sketch_bf16_kernel<4, 1, 8, true>, grid, dim3(256), lds, p);
-    else L.launch_lds(sketch_bf16_kernel<4, 1, 8, false>, grid, dim3(256), lds, p);
-  } else {             // 1024 x 64 tile, 4 waves
-    const size_t lds = sketch_bf16_lds_bytes<2, 2, 16>();
-    if (transposed) L.launch_lds(sketch_bf16_kernel<2, 2, 16, true>, grid, dim3(256), lds, p);
-    else L.launch_lds(sketch_bf16_kernel<2, 2, 16, false>, grid, dim3(256), lds, p);
+  if (sp.rc == 128) {
+    if (transposed) L.launch_lds(sketch8_kernel<true, 4>, grid, dim3(512), (size_t)sketch8_lds_bytes<4>(), p);
+    else L.launch_lds(sketch8_kernel<false, 4>, grid, dim3(512), (size_t)sketch8_lds_bytes<4>(), p);
+  } else {
+    if (transposed) L.launch_lds(sketch8_kernel<true, 2>, grid, dim3(512), (size_t)sketch8_lds_bytes<2>(), p);
+    else L.launch_lds(sketch8_kernel<false, 2>, grid, dim3(512), (size_t)sketch8_lds_bytes<2>(), p);
   }
   if (defer) *defer = ReduceJob{ws, out, channels * d->r, sp.G, d->factor_dtype == ACC_BF16 ? 1 : 0};
   else reduce_partials(d, ws, sp.G, channels * d->r, out, L);

@@ -6,14 +6,12 @@
 // A is X [n, d_in] or dY [n, d_out] (row-major, channels contiguous); S[t, j] is regenerated from the
 // Philox counter (token, column) in registers, directly in MFMA operand layout, and never stored.
 //
-// Work-group = WC x WJ waves; output tile (WC * CWB * 32) channels x (WJ * 32) sketch columns, fp32
-// accumulators in registers for the whole token range of the split (CWB * 16 registers per lane).
-// Tokens stream through LDS in stages of 16 rows (one MFMA k-step), global -> LDS directly, in a ring of
-// NSTAGE stages with NSTAGE - 1 stages in flight: the input is read once from HBM, so enough bytes
-// must be outstanding per CU to cover DRAM latency.  The channel-major MFMA operand is formed from
-// the token-major tile with transposing LDS reads.
-// The contraction runs over tokens, so one Philox call (4 tokens of one column) feeds half an
-// operand register set; every wave generates only the 32 columns it multiplies.
+// Work-group = 8 waves on a tile of 512 channels x 64 or 128 sketch columns, fp32 accumulators in registers
+// for the whole token range of the split.  Tokens stream through LDS in stages of 16 or 32 rows, global ->
+// LDS directly, in a ring with 96 KB in flight: the input is read once from HBM, so enough bytes must be
+// outstanding per CU to cover DRAM latency.  The channel-major MFMA operand is formed from the token-major
+// tile with transposing LDS reads.  The contraction runs over tokens, so one Philox call (4 tokens of one
+// column) feeds half an operand register set.
 #pragma once
 #include "acc_common.h"
 #include "acc_gemm.h"
@@ -65,23 +63,30 @@ __device__ __forceinline__ void store_partial_tile(const f32x16 (&acc)[CWB], flo
   }
 }
 
-template <int WC, int WJ, int CWB, bool TRANSPOSED>
-__global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastParams p) {
-  constexpr int NW = WC * WJ;
-  constexpr int CH = WC * CWB * 32, RC = WJ * 32, BT = 16;
+// 8-wave sketch work-group: tile 512 channels x (WJ * 32) sketch columns, waves WC = 8 / WJ (channels) x WJ
+// (columns), each wave (512 / WC) channels x 32 columns.  An iteration is eight MFMAs per wave:
+//   WJ = 4: 512 x 128 tile, waves 2 x 4, 8 channel blocks x one 16-token k-step  (128 accumulators per lane)
+//   WJ = 2: 512 x  64 tile, waves 4 x 2, 4 channel blocks x two 16-token k-steps ( 64 accumulators per lane)
+// The WC waves that share 32 columns each generate one Philox call per lane and iteration (4 of the 8 * WC / 2
+// tokens a lane's operands need) and trade them through LDS, so S is generated once per work-group, not
+// once per wave.  The narrow tile keeps half as many accumulators per compute unit: a work-group covers
+// twice the tokens and the launch writes (and the fold reads) half as many bytes of partial tiles.
+template <bool TRANSPOSED, int WJ = 4>
+__device__ __forceinline__ void sketch8_tile(const SketchFastParams& p, int b, char* smem) {
+  static_assert(WJ == 4 || WJ == 2, "column groups");
+  constexpr int NW = 8, WC = NW / WJ;
+  constexpr int CH = 512, RC = WJ * 32;
+  constexpr int CWB = CH / (WC * 32);            // channel blocks per wave: 8 or 4
+  constexpr int KS = 8 / CWB;                    // k-steps per iteration: 1 or 2
+  constexpr int BT = 16 * KS;                    // tokens per stage
   constexpr int ROW_BYTES = CH * 2;
-  constexpr int STAGE = BT * ROW_BYTES;
-  constexpr int NSTAGE = 128 * 1024 / STAGE;    // ring of stages in 128 KB of LDS
-  constexpr int DEPTH = NSTAGE - 1;             // stages in flight
-  constexpr int PARTS = ROW_BYTES / 1024;       // 1 KB wave-loads per token row
-  constexpr int LOADS = BT * PARTS / NW;        // wave-loads per wave and stage
-  static_assert(BT * PARTS % NW == 0, "stage/waves");
-  static_assert(CH % 512 == 0, "channel slab must be a multiple of 512");
-  static_assert(CWB % 4 == 0, "the row swizzle permutes groups of four 32-channel blocks");
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  constexpr int STAGE = BT * ROW_BYTES;          // 16 or 32 KB
+  constexpr int NSTAGE = KS == 1 ? 7 : 4;        // ring of 112 or 128 KB,
+  constexpr int DEPTH = NSTAGE - 1;              // 96 KB in flight
+  constexpr int LOADS = BT / NW;                 // 1 KB wave-loads per wave and stage (one per token row)
+  constexpr int XBUF = NSTAGE * STAGE;           // S exchange: 2 slots x KS k-steps x WJ column groups x 64 lanes x 16 B
+  constexpr int XSLOT = KS * WJ * 1024;          // 4 KB either way
 
-  // ---- which tile: pairs of column slices of one (split, slab) share an XCD (blockIdx % 8) ----
-  const int b = blockIdx.x;
   const int js = (b >> 3) % p.n_js;
   const int pair = (b & 7) + 8 * ((b >> 3) / p.n_js);
   if (pair >= p.n_cslab * p.G) return;
@@ -94,18 +99,17 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
   const int64_t c0 = (int64_t)slab * CH;
   int64_t t_end = t_begin + p.tokens_per_split;
   if (t_end > p.n) t_end = p.n;
-  const int NS = t_end > t_begin ? (int)((t_end - t_begin + BT - 1) / BT) : 0;  // stages = k-steps
+  const int NS = t_end > t_begin ? (int)((t_end - t_begin + BT - 1) / BT) : 0;  // stages = iterations
+  if (NS == 0) return;
 
-  // ---- global -> LDS: wave-load L = t * NW + wave covers token row L / PARTS, kilobyte L % PARTS ----
+  // ---- global -> LDS: wave-load t of wave w is token row t * NW + w of the stage ----
   const u32x4 rsrc = make_rsrc(p.A + t_begin * p.lda + c0, ((p.n - t_begin - 1) * p.lda + (p.C - c0)) * 2);
-  uint32_t src[LOADS];
-  uint32_t dst[LOADS];
+  uint32_t src[LOADS], dst[LOADS];
 #pragma unroll
   for (int t = 0; t < LOADS; ++t) {
-    const int L = t * NW + wave, row = L / PARTS, part = L % PARTS;
-    const int chunk = (part * 64 + lane) ^ swz_n(row);   // 16-byte chunk of the row this lane fetches
-    src[t] = (uint32_t)(row * p.lda * 2 + chunk * 16);
-    dst[t] = (uint32_t)(row * ROW_BYTES + part * 1024);
+    const int row = t * NW + wave;
+    src[t] = (uint32_t)(row * p.lda * 2 + ((lane ^ swz_n(row)) << 4));
+    dst[t] = (uint32_t)(row * ROW_BYTES);
   }
   const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
   auto issue_stage = [&](int st, uint32_t stage_lds) {
@@ -113,6 +117,7 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
 #pragma unroll
     for (int t = 0; t < LOADS; ++t) buffer_to_lds_b128(rsrc, src[t], soff, stage_lds + dst[t]);
   };
+  auto wait_oldest_stage = [&]() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LOADS) : "memory"); };
 
   // ---- LDS addresses of the transposing operand reads ----
   // 16-lane group gq = lane / 16 reads channels 16 * (gq & 1) .. and tokens 8 * (gq >> 1) ..; lane i of
@@ -124,36 +129,60 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     const int row = 8 * (gq >> 1) + (i16 >> 2);
-    const int col16 = 2 * (gq & 1) + ((i16 & 3) >> 1);  // 16-byte chunk within the 32-channel block
-    rd_base[v] = row * ROW_BYTES + (((((wc * CWB) & 3) ^ v ^ xr) & 3) << 6) + (col16 << 4) + ((i16 & 1) << 3) +
-                 (((wc * CWB) >> 2) << 8);
+    const int col16 = 2 * (gq & 1) + ((i16 & 3) >> 1);
+    rd_base[v] = row * ROW_BYTES + (((v ^ xr) & 3) << 6) + (col16 << 4) + ((i16 & 1) << 3) + wc * (CWB * 64);
   }
-  // operand of channel block mb (0 .. CWB-1) from stage `st`
-  auto read_block = [&](const char* st, int mb) -> bf16x8 {
-    const int off = (mb >> 2) * 256;
+  // operand of slot s = k-step (s / CWB) of the stage, channel block (s % CWB) of the wave
+  auto read_block = [&](const char* st, int s) -> bf16x8 {
+    const int mb = s % CWB, ks = s / CWB;
+    const int off = (mb >> 2) * 256 + ks * (16 * ROW_BYTES);
     const s16x4 lo = lds_read_tr16_b64(st, rd_base[mb & 3] + off);
     const s16x4 hi = lds_read_tr16_b64(st, rd_base[mb & 3] + off + 4 * ROW_BYTES);
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
 
-  // ---- S operand: lane holds column j, tokens 8 * (lane >> 5) .. + 7 of the k-step ----
+  // ---- S operand: lane holds column j and tokens 8 * (lane >> 5) .. + 7 of a k-step; this wave generates
+  //      tokens 4 * (wc & 1) .. + 3 of them for k-step (wc >> 1) of the iteration (one Philox call) ----
   const uint32_t jcol = (uint32_t)(js * RC + wj * 32 + (lane & 31));
-  const uint64_t q_lane = ((p.sk.row_offset + (uint64_t)t_begin) >> 2) + 2 * (uint64_t)(lane >> 5);
-  auto make_s = [&](int kstep) -> bf16x8 {  // kstep counts 16-token steps from t_begin (prologue only)
-    uint32_t w0[4], w1[4];
-    float z0[4], z1[4];
-    const uint64_t q = q_lane + 4 * (uint64_t)kstep;
-    sketch_words(p.sk.key0, p.sk.key1, q, jcol, w0);
-    sketch_words(p.sk.key0, p.sk.key1, q + 1, jcol, w1);
-    normals_from_words<false>(w0, p.sk.inv_sqrt_r, p.sk.neg2_ln2_over_r, z0);
-    normals_from_words<false>(w1, p.sk.inv_sqrt_r, p.sk.neg2_ln2_over_r, z1);
-    bf16x8 s;
+  const uint64_t q_lane = ((p.sk.row_offset + (uint64_t)t_begin) >> 2) + 2 * (uint64_t)(lane >> 5) +
+                          (uint64_t)(wc & 1) + 4 * (uint64_t)(wc >> 1);
+  char* const xbase = smem + XBUF + wj * 1024 + lane * 16;  // + parity * XSLOT + k-step * WJ * 1024
+  struct HalfGen {
+    uint32_t c[4];
+    float z[4];
+  };
+  auto gen_begin = [&](HalfGen& h, int it) {
+    const uint64_t q = q_lane + (uint64_t)(4 * KS) * (uint64_t)it;
+    h.c[0] = (uint32_t)q; h.c[1] = jcol; h.c[2] = 0u; h.c[3] = (uint32_t)(q >> 32);
+  };
+  auto gen_store = [&](const HalfGen& h, int it) {
+    bf16x4 v;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      s[t] = (bf16)z0[t];
-      s[4 + t] = (bf16)z1[t];
+    for (int t = 0; t < 4; ++t) v[t] = (bf16)h.z[t];
+    *(bf16x4*)(xbase + (it & 1) * XSLOT + (wc >> 1) * (WJ * 1024) + (wc & 1) * 8) = v;
+  };
+  // slice `slot` (0 .. 7) of generating this wave's share of the operands of iteration `it`
+  auto gen_slot = [&](HalfGen& h, int slot, int it) {
+    if (slot == 0) gen_begin(h, it);
+    if (slot < 5) {
+      philox_round(h.c, p.sk.key0, p.sk.key1, 2 * slot);
+      philox_round(h.c, p.sk.key0, p.sk.key1, 2 * slot + 1);
+    } else if (slot == 5) {
+      box_muller_fast(h.c[0], h.c[1], p.sk.neg2_ln2_over_r, h.z[0], h.z[1]);
+    } else if (slot == 6) {
+      box_muller_fast(h.c[2], h.c[3], p.sk.neg2_ln2_over_r, h.z[2], h.z[3]);
+    } else {
+      gen_store(h, it);
     }
-    return s;
+  };
+  struct SOps {
+    bf16x8 s[KS];
+  };
+  auto read_s = [&](int it) -> SOps {  // all shares of the operands of iteration `it`
+    SOps o;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) o.s[ks] = *(const bf16x8*)(xbase + (it & 1) * XSLOT + ks * (WJ * 1024));
+    return o;
   };
 
   f32x16 acc[CWB];
@@ -162,107 +191,67 @@ __global__ __launch_bounds__(WC* WJ * 64) void sketch_bf16_kernel(SketchFastPara
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
 
-  // One k-step (16 tokens) in CWB slots.  Slot mb issues MFMA mb on operands already in registers, the
-  // two transposing reads of operand mb of the following k-step, and one slice of the generation of
-  // the S operand of the following k-step (10 Philox rounds on two counters, 4 Box-Muller pairs, pack).
-  // Fences between slots keep this order: the matrix pipe and the vector ALU then run concurrently
-  // instead of one after the other, and every LDS read has a whole k-step to return.
-  static_assert(CWB >= 16 || CWB == 8, "the S generation is spread over 16 slots, or packed into 8");
-  struct SGen {
-    uint32_t c[2][4];
-    float z[8];
-  };
-  auto sgen_slot = [&](SGen& g, int slot, int kstep, bf16x8& out) {
-    if (slot == 0) {
-      const uint64_t q = q_lane + 4 * (uint64_t)kstep;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        g.c[h][0] = (uint32_t)(q + h); g.c[h][1] = jcol; g.c[h][2] = 0u; g.c[h][3] = (uint32_t)((q + h) >> 32);
-      }
-    }
-    if constexpr (CWB >= 16) {
-      if (slot < 10) {
-        philox_round(g.c[0], p.sk.key0, p.sk.key1, slot);
-        philox_round(g.c[1], p.sk.key0, p.sk.key1, slot);
-      } else if (slot < 14) {
-        const int pr = slot - 10, h = pr >> 1, a = (pr & 1) * 2;
-        box_muller_fast(g.c[h][a], g.c[h][a + 1], p.sk.neg2_ln2_over_r, g.z[4 * h + a], g.z[4 * h + a + 1]);
-      } else if (slot == 14) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
-      }
-    } else {  // 8 slots: two rounds, then two Box-Muller pairs per slot
-      if (slot < 5) {
-#pragma unroll
-        for (int rr = 2 * slot; rr < 2 * slot + 2; ++rr) {
-          philox_round(g.c[0], p.sk.key0, p.sk.key1, rr);
-          philox_round(g.c[1], p.sk.key0, p.sk.key1, rr);
-        }
-      } else if (slot < 7) {
-        const int h = slot - 5;
-        box_muller_fast(g.c[h][0], g.c[h][1], p.sk.neg2_ln2_over_r, g.z[4 * h], g.z[4 * h + 1]);
-        box_muller_fast(g.c[h][2], g.c[h][3], p.sk.neg2_ln2_over_r, g.z[4 * h + 2], g.z[4 * h + 3]);
-      } else {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) out[t] = (bf16)g.z[t];
-      }
-    }
-  };
-  auto kstep_slots = [&](const bf16x8(&af)[CWB], bf16x8 sf, const char* rd_stage, bf16x8(&nf)[CWB], SGen& g,
-                         int gen_kstep, bf16x8& s_next) {
-#pragma unroll
-    for (int mb = 0; mb < CWB; ++mb) {
-      if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf, af[mb], acc[mb], 0, 0, 0);
-      else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mb], sf, acc[mb], 0, 0, 0);
-      nf[mb] = read_block(rd_stage, mb);
-      sgen_slot(g, mb, gen_kstep, s_next);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  // s_waitcnt vmcnt((DEPTH - 1) * LOADS): everything but the DEPTH - 1 youngest stages has landed
-  auto wait_oldest_stage = [&]() {
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DEPTH - 1) * LOADS) : "memory");
-  };
-  // One iteration = one k-step t: start the transfer of stage t + DEPTH into the slot stage t - 1 used,
-  // make sure stage t + 1 has landed for every wave, then multiply k-step t while reading t + 1.
-  // Branch-free: past the end the last stage is fetched again into a slot nobody reads.
-  auto iteration = [&](int t, const bf16x8(&af)[CWB], bf16x8 sf, bf16x8(&nf)[CWB], SGen& g, bf16x8& s_next) {
+  // One iteration = stage t.  Start the transfer of stage t + DEPTH into the slot stage t - 1 used,
+  // make sure stage t + 1 (and the S shares of iteration t + 1) are there for every wave, then in 8 slots:
+  // MFMA on the operands in registers, the reads of the operands of iteration t + 1, and a slice of this
+  // wave's share of S for iteration t + 2.  Branch-free: past the end the last stage is fetched again.
+  HalfGen hg;
+  auto iteration = [&](int t, const bf16x8(&af)[8], const SOps& sf, bf16x8(&nf)[8], SOps& s_next) {
     const int t_load = t + DEPTH < NS ? t + DEPTH : NS - 1;
     __builtin_amdgcn_sched_barrier(0);
     issue_stage(t_load, smem_lds + ((t + DEPTH) % NSTAGE) * STAGE);
     wait_oldest_stage();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    kstep_slots(af, sf, smem + ((t + 1) % NSTAGE) * STAGE, nf, g, t + 1, s_next);
+    const char* rd_stage = smem + ((t + 1) % NSTAGE) * STAGE;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int mb = s % CWB, ks = s / CWB;
+      if (TRANSPOSED) acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sf.s[ks], af[s], acc[mb], 0, 0, 0);
+      else acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s], sf.s[ks], acc[mb], 0, 0, 0);
+      if (s == 0) s_next = read_s(t + 1);
+      nf[s] = read_block(rd_stage, s);
+      gen_slot(hg, s, t + 2);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
 
-  if (NS > 0) {
-    bf16x8 fa[CWB], fb[CWB];
-    SGen gen;
+  bf16x8 fa[8], fb[8];
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) issue_stage(d < NS ? d : NS - 1, smem_lds + d * STAGE);
-    bf16x8 s_a = make_s(0), s_b = s_a;
-    wait_oldest_stage();
-    __syncthreads();
+  for (int d = 0; d < DEPTH; ++d) issue_stage(d < NS ? d : NS - 1, smem_lds + d * STAGE);
 #pragma unroll
-    for (int mb = 0; mb < CWB; ++mb) fa[mb] = read_block(smem, mb);
-    int t = 0;
-    for (; t + 1 < NS; t += 2) {
-      iteration(t, fa, s_a, fb, gen, s_b);
-      iteration(t + 1, fb, s_b, fa, gen, s_a);
-    }
-    if (t < NS) iteration(t, fa, s_a, fb, gen, s_b);
+  for (int k = 0; k < 2; ++k) {  // this wave's shares of the operands of iterations 0 and 1
+#pragma unroll
+    for (int slot = 0; slot < 8; ++slot) gen_slot(hg, slot, k);
   }
+  wait_oldest_stage();
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < 8; ++s) fa[s] = read_block(smem, s);
+  SOps s_a = read_s(0), s_b = s_a;
+  int t = 0;
+  for (; t + 1 < NS; t += 2) {
+    iteration(t, fa, s_a, fb, s_b);
+    iteration(t + 1, fb, s_b, fa, s_a);
+  }
+  if (t < NS) iteration(t, fa, s_a, fb, s_b);
   wait_vmcnt0();  // no transfer may still be in flight when the work-group's LDS is released
 
-  // ---- store the fp32 partial tile ----
   store_partial_tile<TRANSPOSED, CWB>(acc, p.part + (int64_t)g * p.C * p.r, p.C, p.r, c0 + wc * CWB * 32,
                                       js * RC + wj * 32, lane);
 }
 
-template <int WC, int WJ, int CWB>
-constexpr int sketch_bf16_lds_bytes() {
-  return 128 * 1024;
+// The 8-wave sketch tile as a kernel of its own: grid = 8 * n_js * ceil(n_cslab * G / 8) work-groups.
+template <bool TRANSPOSED, int WJ = 4>
+__global__ __launch_bounds__(512) void sketch8_kernel(SketchFastParams sp) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  sketch8_tile<TRANSPOSED, WJ>(sp, blockIdx.x, smem);
+}
+
+// Dynamic LDS of sketch8_kernel: the stage ring plus the 8 KB S exchange.
+template <int WJ>
+constexpr int sketch8_lds_bytes() {
+  return WJ == 4 ? 128 * 1024 : 136 * 1024;
 }
 
 }  // namespace acc

@@ -142,11 +142,14 @@ FAST_SHAPES = [
     # shapes the tuned bf16 kernels take (K % 64 == 0, r % 64 == 0) with ragged token / column tails
     (1000, 512, 640, 128),      # 128x128 tiles, ragged M
     (4100, 1024, 3080, 256),    # 256x256 tiles, ragged M and N
-    (2500, 576, 1096, 64),      # rank-64 sketch tile, ragged channel slab (576 < 1024)
-    (8192, 2048, 2048, 192),    # r % 64 == 0 but r % 128 != 0
-    (33, 64, 64, 64),           # a single partial stage
-    (4100, 1024, 3080, 32),     # the paper's rank 32: 1024 x 32 sketch tile, up to 64 token splits
-    (20000, 3072, 1024, 16),    # rank 16 with many token splits (G = 64) and three channel slabs
+    (2500, 576, 1096, 64),      # one column slice of the 512 x 64 sketch tile, ragged second channel slab
+    (8192, 2048, 2048, 192),    # three column slices
+    (33, 64, 64, 64),           # a single stage, partly filled
+    (65, 512, 512, 64),         # three stages: both bodies of the unrolled loop and the odd tail
+    (4100, 1024, 3080, 32),     # the paper's rank 32: the second column group of the tile is masked
+    (20000, 3072, 1024, 16),    # rank 16, 42 token splits over six channel slabs
+    (5000, 1536, 520, 96),      # a half-empty last column slice, ragged tokens and channels
+    (3000, 512, 1024, 320),     # five column slices per input panel
 ]
 
 
