@@ -254,6 +254,13 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
                            // fewer operand bytes from LDS per flop than 8 waves of 128 x 64: +0.4 % on a step
     const unsigned grid = gemm_bf16_plan(p, 256, 256);
     p.red_stride = (int64_t)grid * 256 * 4;
+    if constexpr (sizeof(TC) == 2) {
+      if (!accumulate) {  // the epilogue folded into the last K tile
+        L.launch_lds(gemm_bf16_kernel<2, 2, 4, 4, KMAJ, TC, true>, dim3(grid), dim3(256),
+                     (size_t)gemm_bf16_lds_bytes<2, 2, 4, 4>(), p);
+        return;
+      }
+    }
     L.launch_lds(gemm_bf16_kernel<2, 2, 4, 4, KMAJ, TC>, dim3(grid), dim3(256),
                  (size_t)gemm_bf16_lds_bytes<2, 2, 4, 4>(), p);
   } else {                 // 128 x 128 tiles, 4 waves
