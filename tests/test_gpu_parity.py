@@ -172,6 +172,13 @@ def test_tuned_kernels_fp32_dw_and_strides(acc):
     _check(acc, lin, dw_dtype=0, pad=(64, 8, 72), row_offset=4 * 77, seed=0xABCDEF0123)
 
 
+def test_big_tile_gemm_with_strides(acc):
+    """256 x 256 tiles (the epilogue runs inside the last K tile and stores through a buffer resource) on strided
+    X / dX, W and Y / dY with ragged M and N: the padding columns of Y and dX keep their contents."""
+    lin = inputs.Linear("big_strided", 4100, 1024, 3080, 128, dtype="bf16")
+    _check(acc, lin, pad=(40, 8, 24))
+
+
 def test_one_launch_flag_gives_identical_results(acc):
     """ACC_FLAG_ONE_LAUNCH interleaves GEMM and sketch work-groups in one grid: same outputs, bit for bit
     for the exact products, within tolerance of the oracle for the factors."""
