@@ -198,7 +198,7 @@ def test_one_launch_flag_gives_identical_results(acc):
     (777, 520, 264, 48, "bf16"),       # generic kernels, bfloat16
     (1000, 512, 640, 128, "bf16"),     # tuned kernels, 128 x 128 tiles
     (4100, 1024, 3080, 256, "bf16"),   # tuned kernels, 256 x 256 tiles, ragged M and N
-    (2500, 576, 1096, 64, "bf16"),     # 4-wave sketch tile
+    (2500, 576, 1096, 64, "bf16"),     # one column slice of the sketch tile, ragged channel slab
 ])
 def test_weight_out_in_orientation_and_bias_gradient(acc, n, d_in, d_out, r, dtype):
     lin = inputs.Linear(f"oi_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype=dtype)
@@ -308,12 +308,16 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(acc):
             assert torch.equal(outs[k], eager[k]), (rep, k)
 
 
-@pytest.mark.parametrize("n,d_in,d_out,r", [(1000, 512, 640, 128), (777, 520, 264, 48), (2500, 576, 1096, 64)])
-def test_row_offsets_crossing_2_pow_34(acc, n, d_in, d_out, r):
-    """A shard whose global token indices cross 2^34: the high bits move into the fourth counter word
-    (tuned 8-wave and 4-wave sketch kernels and the generic one)."""
-    lin = inputs.Linear(f"hi_offset_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16", seed=0x5EED5EED5EED)
-    _check(acc, lin, row_offset=(1 << 34) - 512)
+@pytest.mark.parametrize("n,d_in,d_out,r,dtype,one_launch", [
+    (1000, 512, 640, 128, "bf16", False),   # 512 x 64 sketch tile
+    (1000, 512, 640, 128, "bf16", True),    # the 512 x 128 tile that the one-launch flag selects
+    (777, 520, 264, 48, "bf16", False),     # surplus sketch columns masked
+    (700, 72, 40, 16, "f32", False),        # generic kernels
+])
+def test_row_offsets_crossing_2_pow_34(acc, n, d_in, d_out, r, dtype, one_launch):
+    """A shard whose global token indices cross 2^34: the high bits move into the fourth counter word."""
+    lin = inputs.Linear(f"hi_offset_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype=dtype, seed=0x5EED5EED5EED)
+    _check(acc, lin, row_offset=(1 << 34) - 512, flags=acc.ACC_FLAG_ONE_LAUNCH if one_launch else 0)
 
 
 def test_all_zero_inputs_give_exact_zeros(acc):
