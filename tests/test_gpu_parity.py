@@ -179,6 +179,18 @@ def test_big_tile_gemm_with_strides(acc):
     _check(acc, lin, pad=(40, 8, 24))
 
 
+@pytest.mark.parametrize("n,d_in,d_out,r,pad", [
+    (16284, 192, 3072, 64, (0, 0, 0)),      # forward: three K tiles (the minimum), ragged last row of tiles
+    (16384, 256, 3072, 64, (64, 8, 24)),    # four K tiles (stage parity unchanged from tile to tile), strided
+    (16384, 320, 3072, 64, (0, 0, 0)),      # five K tiles (stage parity alternates)
+    (16384, 3072, 3136, 64, (0, 0, 0)),     # backward: 49 K tiles, three output tiles per work-group
+])
+def test_persistent_gemm_across_output_tiles(acc, n, d_in, d_out, r, pad):
+    """More than 256 output tiles of 256 x 256 without padding slots in the tile map: 256 persistent
+    work-groups whose K pipeline runs across the tile boundary (next tile requested inside the last K tile)."""
+    _check(acc, inputs.Linear(f"persist_{n}x{d_in}x{d_out}", n, d_in, d_out, r, dtype="bf16"), pad=pad)
+
+
 def test_one_launch_flag_gives_identical_results(acc):
     """ACC_FLAG_ONE_LAUNCH interleaves GEMM and sketch work-groups in one grid: same outputs, bit for bit
     for the exact products, within tolerance of the oracle for the factors."""
