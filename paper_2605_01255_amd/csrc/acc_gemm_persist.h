@@ -8,7 +8,8 @@
 //
 // LDS: two 64 KB stages + 32 KB of staging regions for the read-out (two 4 KB regions per wave, rows of
 // 128 bytes with the 16-byte chunk index XOR-ed with the row so that writes and read-backs spread over the banks).
-// The first k-step of every tile multiplies onto zero, so the accumulators are never cleared.
+// The first k-step of every tile multiplies onto zero, so the accumulators are never cleared; it also carries the
+// read-out of the previous tile's last two units, which were final only after that tile's last MFMA.
 // Restrictions (the host checks them): bf16 output, no accumulation into C, no K split, every slot of the
 // XCD tile map is a real tile, K >= 192.
 #pragma once
@@ -115,10 +116,68 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
 
   TileRef cur_t = tile_ref(blockIdx.x);
 
+  // ---- read-out of a finished 32 x 64 unit (see gemm_bf16_tile) ----
+  bf16* __restrict__ C = (bf16*)p.C;
+  const int e_row = lane >> 3, e_ch = lane & 7;
+  char* const region = smem + 2 * STAGE + wave * (2 * UNIT_B);
+  int w_addr[8];  // staging address of 16-byte chunk c of this lane's row (+ 8 bytes for the upper lane half)
+#pragma unroll
+  for (int c = 0; c < 8; ++c) w_addr[c] = lrow * 128 + ((c ^ (lrow & 7)) << 4) + kg * 8;
+  const int r_addr = e_row * 128 + ((e_ch ^ e_row) << 4);
+  const uint32_t c_row_bytes = (uint32_t)(p.ldc * 2);
+  auto wave_fence = [&]() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  // output addressing of the tile that is being read out (set by final_tile, still used in the first k-step
+  // of the next tile, which carries the end of the read-out)
+  __amdgpu_buffer_rsrc_t c_rs;
+  uint32_t c_voff[2];
+  auto set_output = [&](const TileRef& t) {
+    const int64_t gm_base = t.m0 + wm * TM * 32, gn_base = t.n0 + wn * TN * 32;
+    int64_t c_rows = p.M - gm_base;
+    if (c_rows > TM * 32) c_rows = TM * 32;
+    const int64_t c_bytes = (c_rows > 0 && gn_base < p.N) ? ((c_rows - 1) * p.ldc + (p.N - gn_base)) * 2 : 0;
+    c_rs = __builtin_amdgcn_make_buffer_rsrc((void*)(C + gm_base * p.ldc + gn_base), 0, (int)(uint32_t)c_bytes,
+                                             0x00020000);
+#pragma unroll
+    for (int jh = 0; jh < 2; ++jh)
+      c_voff[jh] = gn_base + jh * 64 + e_ch * 8 < p.N ? (uint32_t)((e_row * p.ldc + jh * 64 + e_ch * 8) * 2)
+                                                      : 0xFFFFFFF0u;  // columns past N: out of range, dropped
+  };
+  auto stage_write = [&](int u, int k) {  // unit u = 2 * i + jh; write k: block column k / 4, register group k % 4
+    const int i = u >> 1, j = 2 * (u & 1) + (k >> 2), g4 = k & 3;
+    bf16x4 v;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) v[t] = (bf16)acc[i][j][g4 * 4 + t];
+    *(bf16x4*)(region + (u & 1) * UNIT_B + w_addr[(k >> 2) * 4 + g4]) = v;
+  };
+  auto read_back = [&](int u, int t) -> u32x4 {
+    return *(const u32x4*)(region + (u & 1) * UNIT_B + t * 1024 + r_addr);
+  };
+  auto store_back = [&](int u, int t, u32x4 v) {
+    const uint32_t soff = (uint32_t)((u >> 1) * 32 + t * 8) * c_row_bytes;
+    __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff[u & 1], soff, 0);
+  };
+  u32x4 back[4];
+  // End of the read-out of a tile (units 6 and 7), as work for the sixteen slots of the next tile's first k-step:
+  // unit 7's accumulators (block row 3, columns 2 and 3) are read before that k-step's MFMAs 14 and 15 restart them.
+  auto drain_slot = [&](int q) {
+    if (q == 0) wave_fence();
+    if (q < 8) stage_write(7, q);
+    if (q < 4) back[q] = read_back(6, q);
+    else if (q < 8) store_back(6, q - 4, back[q - 4]);
+    if (q == 8) wave_fence();
+    if (q >= 8 && q < 12) back[q - 8] = read_back(7, q - 8);
+    if (q >= 12) store_back(7, q - 12, back[q - 12]);
+  };
+  auto no_extra = [](int) {};
+
   // One k-step (same order as gemm_bf16_tile's): MFMA q carries one operand read of the next k-step on even q and
   // one wave-load on odd q.  zero: the products start the accumulators instead of adding to them.
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s, bf16x8(&na)[TM],
-                   bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, uint32_t nxt, auto zero) {
+                   bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, uint32_t nxt, auto zero, auto&& extra) {
 #pragma unroll
     for (int q = 0; q < NM; ++q) {
       const int i = q / TN, j = q % TN;
@@ -136,39 +195,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
       } else if (q / 2 < g_count) {
         issue_one(cur_t, g_first + q / 2, kt_next, nxt);
       }
+      extra(q);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
   // One K tile in the steady state; par: stage of this tile's K tile 0.  ahead: the tile after next exists
   // (its first half is requested in the last k-step).  first: K tile 0 of an output tile.
-  auto ktile = [&](int kt, int par, auto ahead, auto first) {
+  auto ktile = [&](int kt, int par, auto ahead, auto first, auto carry) {
     const int sc = (kt + par) & 1;
     const char* cur = smem + sc * STAGE;
     const char* nxt = smem + (sc ^ 1) * STAGE;
     __builtin_amdgcn_sched_barrier(0);
-    kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 0, 0, 0, 0u, std::false_type{});
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 0, 0, 0, 0u, std::false_type{});
+    if constexpr (decltype(carry)::value)
+      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first, drain_slot);
+    else
+      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first, no_extra);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 0, 0, 0, 0u, std::false_type{}, no_extra);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 0, 0, 0, 0u, std::false_type{}, no_extra);
     wait_vmcnt0();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
     kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, decltype(ahead)::value ? G_PER_STEP : 0, kt + 2,
-          smem_lds + sc * STAGE, std::false_type{});
-  };
-
-  // ---- read-out of a finished 32 x 64 unit (see gemm_bf16_tile) ----
-  bf16* __restrict__ C = (bf16*)p.C;
-  const int e_row = lane >> 3, e_ch = lane & 7;
-  char* const region = smem + 2 * STAGE + wave * (2 * UNIT_B);
-  int w_addr[8];  // staging address of 16-byte chunk c of this lane's row (+ 8 bytes for the upper lane half)
-#pragma unroll
-  for (int c = 0; c < 8; ++c) w_addr[c] = lrow * 128 + ((c ^ (lrow & 7)) << 4) + kg * 8;
-  const int r_addr = e_row * 128 + ((e_ch ^ e_row) << 4);
-  const uint32_t c_row_bytes = (uint32_t)(p.ldc * 2);
-  auto wave_fence = [&]() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+          smem_lds + sc * STAGE, std::false_type{}, no_extra);
   };
 
   // Last K tile of an output tile.  prefetch: another output tile (next_t) follows.
@@ -178,32 +226,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
     const char* cur = smem + sc * STAGE;
     const char* other = smem + (sc ^ 1) * STAGE;
     const uint32_t cur_lds = smem_lds + sc * STAGE, other_lds = smem_lds + (sc ^ 1) * STAGE;
-    const int64_t gm_base = cur_t.m0 + wm * TM * 32, gn_base = cur_t.n0 + wn * TN * 32;
-    int64_t c_rows = p.M - gm_base;
-    if (c_rows > TM * 32) c_rows = TM * 32;
-    const int64_t c_bytes = (c_rows > 0 && gn_base < p.N) ? ((c_rows - 1) * p.ldc + (p.N - gn_base)) * 2 : 0;
-    const __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(C + gm_base * p.ldc + gn_base), 0, (int)(uint32_t)c_bytes, 0x00020000);
-    uint32_t c_voff[2];
-#pragma unroll
-    for (int jh = 0; jh < 2; ++jh)
-      c_voff[jh] = gn_base + jh * 64 + e_ch * 8 < p.N ? (uint32_t)((e_row * p.ldc + jh * 64 + e_ch * 8) * 2)
-                                                      : 0xFFFFFFF0u;
-    auto stage_write = [&](int u, int k) {  // unit u = 2 * i + jh; write k: block column k / 4, register group k % 4
-      const int i = u >> 1, j = 2 * (u & 1) + (k >> 2), g4 = k & 3;
-      bf16x4 v;
-#pragma unroll
-      for (int t = 0; t < 4; ++t) v[t] = (bf16)acc[i][j][g4 * 4 + t];
-      *(bf16x4*)(region + (u & 1) * UNIT_B + w_addr[(k >> 2) * 4 + g4]) = v;
-    };
-    auto read_back = [&](int u, int t) -> u32x4 {
-      return *(const u32x4*)(region + (u & 1) * UNIT_B + t * 1024 + r_addr);
-    };
-    auto store_back = [&](int u, int t, u32x4 v) {
-      const uint32_t soff = (uint32_t)((u >> 1) * 32 + t * 8) * c_row_bytes;
-      __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff[u & 1], soff, 0);
-    };
-
+    set_output(cur_t);
     bf16x8 aq[2][4], bq[4][TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) bq[0][j] = bfr[0][j];
@@ -215,7 +238,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
       bq[ks][1] = read_b(cur, ks, 1);
     }
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 back[4];
 #pragma unroll
     for (int h = 0; h < 8; ++h) {
       const int i = h >> 1, jh = h & 1;
@@ -245,18 +267,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    u32x4 back7[4];
+    if constexpr (!PF) {  // no tile follows: units 6 and 7 are read out here (else in the next tile's first k-step)
 #pragma unroll
-    for (int k = 0; k < 8; ++k) stage_write(7, k);
-    wave_fence();
-#pragma unroll
-    for (int t = 0; t < 4; ++t) back[t] = read_back(6, t);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) back7[t] = read_back(7, t);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) store_back(6, t, back[t]);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) store_back(7, t, back7[t]);
+      for (int q = 0; q < 16; ++q) drain_slot(q);
+    }
     __builtin_amdgcn_sched_barrier(0);
   };
 
@@ -291,10 +305,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   for (int idx = blockIdx.x;;) {
     const int next_idx = idx + (int)gridDim.x;
     const bool has_next = next_idx < n_slots;
-    ktile(0, par, std::true_type{}, std::true_type{});
+    if (idx == (int)blockIdx.x) ktile(0, par, std::true_type{}, std::true_type{}, std::false_type{});
+    else ktile(0, par, std::true_type{}, std::true_type{}, std::true_type{});  // carries the end of the last read-out
     int kt = 1;
-    for (; kt + 2 < KT; ++kt) ktile(kt, par, std::true_type{}, std::false_type{});
-    ktile(kt, par, std::false_type{}, std::false_type{});
+    for (; kt + 2 < KT; ++kt) ktile(kt, par, std::true_type{}, std::false_type{}, std::false_type{});
+    ktile(kt, par, std::false_type{}, std::false_type{}, std::false_type{});
     ++kt;
     if (!has_next) {
       final_tile(kt, par, cur_t, std::false_type{});
