@@ -81,19 +81,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   int a_rd[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) a_rd[i] = (wm * TM * 32 + i * 32 + lrow) * 128;
-  int b_rd[TN][2];
+  int b_rd[TN];  // N-contiguous B: first of the two transposing reads; the second is 4 k-rows further (same swizzle)
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     if (B_KMAJOR) {
-      b_rd[j][0] = b_rd[j][1] = A_BYTES + (wn * TN * 32 + j * 32 + lrow) * 128;
+      b_rd[j] = A_BYTES + (wn * TN * 32 + j * 32 + lrow) * 128;
     } else {
       const int g = lane >> 4, i16 = lane & 15;
       const int n_off = (wn * TN + j) * 32 + 16 * (g & 1) + 4 * (i16 & 3);
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int krow = 8 * (g >> 1) + 4 * h + (i16 >> 2);
-        b_rd[j][h] = A_BYTES + krow * (BN * 2) + (((n_off >> 3) ^ swz_n(krow)) << 4) + (n_off & 7) * 2;
-      }
+      const int krow = 8 * (g >> 1) + (i16 >> 2);
+      b_rd[j] = A_BYTES + krow * (BN * 2) + (((n_off >> 3) ^ swz_n(krow)) << 4) + (n_off & 7) * 2;
     }
   }
   const int a_swz = swz(lrow);
@@ -102,10 +99,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   };
   auto read_b = [&](const char* st, int s, int j) -> bf16x8 {
     if (B_KMAJOR) {
-      return lds_read_b128(st, b_rd[j][0] + (((2 * s + kg) ^ a_swz) << 4));
+      return lds_read_b128(st, b_rd[j] + (((2 * s + kg) ^ a_swz) << 4));
     } else {
-      const s16x4 lo = lds_read_tr16_b64(st, b_rd[j][0] + 16 * s * (BN * 2));
-      const s16x4 hi = lds_read_tr16_b64(st, b_rd[j][1] + 16 * s * (BN * 2));
+      const s16x4 lo = lds_read_tr16_b64(st, b_rd[j] + 16 * s * (BN * 2));
+      const s16x4 hi = lds_read_tr16_b64(st, b_rd[j] + (16 * s + 4) * (BN * 2));
       return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
     }
   };
@@ -120,9 +117,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   bf16* __restrict__ C = (bf16*)p.C;
   const int e_row = lane >> 3, e_ch = lane & 7;
   char* const region = smem + 2 * STAGE + wave * (2 * UNIT_B);
-  int w_addr[8];  // staging address of 16-byte chunk c of this lane's row (+ 8 bytes for the upper lane half)
-#pragma unroll
-  for (int c = 0; c < 8; ++c) w_addr[c] = lrow * 128 + ((c ^ (lrow & 7)) << 4) + kg * 8;
+  // staging address of 16-byte chunk c of this lane's row: w_base ^ (c << 4) (the region is 4 KB aligned and the
+  // chunk index sits in bits 4 .. 6, so the XOR of the swizzle can be applied to the whole address)
+  const uint32_t w_base = (uint32_t)(uintptr_t)region + lrow * 128 + ((lrow & 7) << 4) + kg * 8;
   const int r_addr = e_row * 128 + ((e_ch ^ e_row) << 4);
   const uint32_t c_row_bytes = (uint32_t)(p.ldc * 2);
   auto wave_fence = [&]() {
@@ -151,7 +148,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
     bf16x4 v;
 #pragma unroll
     for (int t = 0; t < 4; ++t) v[t] = (bf16)acc[i][j][g4 * 4 + t];
-    *(bf16x4*)(region + (u & 1) * UNIT_B + w_addr[(k >> 2) * 4 + g4]) = v;
+    typedef bf16x4 __attribute__((address_space(3))) * lds_bf16x4_ptr;
+    *(lds_bf16x4_ptr)(uintptr_t)((w_base ^ (uint32_t)(((k >> 2) * 4 + g4) << 4)) + (u & 1) * UNIT_B) = v;
   };
   auto read_back = [&](int u, int t) -> u32x4 {
     return *(const u32x4*)(region + (u & 1) * UNIT_B + t * 1024 + r_addr);
