@@ -1,9 +1,10 @@
 // Persistent form of the tuned bf16 GEMM (steps F1, B1) for shapes with several rounds of 256 x 256 tiles:
 // 256 work-groups (one per compute unit) walk over the output tiles b, b + 256, b + 512, ... and the K
 // pipeline runs across the tile boundary.  The last K tile of a tile carries the read-out of the finished
-// accumulators (as in gemm_bf16_tile's FOLD path) and, in the same slots, requests the first K tile of the next
-// output tile into the stage that has fallen idle and half of its second K tile into the stage it frees
-// itself, so a new tile starts with its operands in LDS: no launch of a new work-group, no burst of first
+// accumulators (as in gemm_bf16_tile's FOLD path); the first K tile of the next output tile is requested in the
+// cadence of any other K tile (first half in the last k-step of the last but one K tile, second half in the
+// first k-step of the last), half of its second K tile goes into the stage the last K tile frees itself, so a
+// new tile starts with its operands in LDS: no launch of a new work-group, no burst of first
 // transfers from every compute unit at once, no wait for them.
 //
 // LDS: two 64 KB stages + 32 KB of staging regions for the read-out (two 4 KB regions per wave, rows of
@@ -175,7 +176,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   // One k-step (same order as gemm_bf16_tile's): MFMA q carries one operand read of the next k-step on even q and
   // one wave-load on odd q.  zero: the products start the accumulators instead of adding to them.
   auto kstep = [&](const bf16x8(&ca)[TM], const bf16x8(&cb)[TN], const char* rd_stage, int rd_s, bf16x8(&na)[TM],
-                   bf16x8(&nb)[TN], int g_first, int g_count, int kt_next, uint32_t nxt, auto zero, auto&& extra) {
+                   bf16x8(&nb)[TN], const TileRef& tr, int g_first, int g_count, int kt_next, uint32_t nxt, auto zero,
+                   auto&& extra) {
 #pragma unroll
     for (int q = 0; q < NM; ++q) {
       const int i = q / TN, j = q % TN;
@@ -191,30 +193,38 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
         else if (r <= TN) nb[r - 1] = read_b(rd_stage, rd_s, r - 1);
         else na[r - TN] = read_a(rd_stage, rd_s, r - TN);
       } else if (q / 2 < g_count) {
-        issue_one(cur_t, g_first + q / 2, kt_next, nxt);
+        issue_one(tr, g_first + q / 2, kt_next, nxt);
       }
       extra(q);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // One K tile in the steady state; par: stage of this tile's K tile 0.  ahead: the tile after next exists
-  // (its first half is requested in the last k-step).  first: K tile 0 of an output tile.
-  auto ktile = [&](int kt, int par, auto ahead, auto first, auto carry) {
+  // One K tile in the steady state; par: stage of this tile's K tile 0.  ahead: what the last k-step requests
+  // into the stage this K tile frees: 1 = first half of K tile kt + 2, 2 = first half of K tile 0 of the next
+  // output tile (kt is then the last but one K tile), 0 = nothing.  first: K tile 0 of an output tile.  carry:
+  // the first k-step also finishes the read-out of the previous output tile.
+  auto ktile = [&](int kt, int par, auto ahead, auto first, auto carry, const TileRef& next_t, int next_count) {
+    constexpr int AHEAD = decltype(ahead)::value;
     const int sc = (kt + par) & 1;
     const char* cur = smem + sc * STAGE;
     const char* nxt = smem + (sc ^ 1) * STAGE;
     __builtin_amdgcn_sched_barrier(0);
     if constexpr (decltype(carry)::value)
-      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first, drain_slot);
+      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], cur_t, G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first,
+            drain_slot);
     else
-      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first, no_extra);
-    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], 0, 0, 0, 0u, std::false_type{}, no_extra);
-    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], 0, 0, 0, 0u, std::false_type{}, no_extra);
+      kstep(af[0], bfr[0], cur, 1, af[1], bfr[1], cur_t, G_PER_STEP, G_PER_STEP, kt + 1, smem_lds + (sc ^ 1) * STAGE, first,
+            no_extra);
+    kstep(af[1], bfr[1], cur, 2, af[0], bfr[0], cur_t, 0, 0, 0, 0u, std::false_type{}, no_extra);
+    kstep(af[0], bfr[0], cur, 3, af[1], bfr[1], cur_t, 0, 0, 0, 0u, std::false_type{}, no_extra);
     wait_vmcnt0();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], 0, decltype(ahead)::value ? G_PER_STEP : 0, kt + 2,
-          smem_lds + sc * STAGE, std::false_type{}, no_extra);
+    if constexpr (AHEAD == 2)  // next_count: G_PER_STEP, or 0 when no output tile follows
+      kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], next_t, 0, next_count, 0, smem_lds + sc * STAGE, std::false_type{}, no_extra);
+    else
+      kstep(af[1], bfr[1], nxt, 0, af[0], bfr[0], cur_t, 0, AHEAD == 1 ? G_PER_STEP : 0, kt + 2, smem_lds + sc * STAGE,
+            std::false_type{}, no_extra);
   };
 
   // Last K tile of an output tile.  prefetch: another output tile (next_t) follows.
@@ -241,8 +251,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
       const int i = h >> 1, jh = h & 1;
       if (h >= 2) wave_fence();
       if (PF && h == 6) {
-        // The next tile's K tile 0 (requested in the first sixteen slots) has landed for this wave: everything
-        // but the sixteen stores issued since then is complete.  After the barrier it has landed for every wave,
+        // The next tile's K tile 0 (requested in the last k-step of the K tile before this one and in this one's
+        // first eight slots) has landed for this wave: everything but the sixteen stores issued since is complete.  After the barrier it has landed for every wave,
         // and every wave has read all it needs from `cur`, which then takes half of the next K tile 1.
         asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
         __syncthreads();
@@ -255,7 +265,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
                                                             acc[i][j], 0, 0, 0);
         if (h == 0 && k < 6) bq[1 + k / 2][2 + (k & 1)] = read_b(cur, 1 + k / 2, 2 + (k & 1));
         if (jh == 0 && i < 3 && k >= 5) aq[(i + 1) & 1][k - 4] = read_a(cur, k - 4, i + 1);
-        if (PF && h < 2) issue_one(next_t, h * 8 + k, 0, other_lds);
+        if (PF && h == 0) issue_one(next_t, G_PER_STEP + k, 0, other_lds);  // second half; the first went out a k-step ago
         if (PF && h == 6) issue_one(next_t, k, 1, cur_lds);
         if (PF && h == 6 && k < 4) af[1][k] = read_a(other, 0, k);
         if (PF && h == 6 && k >= 4) bfr[1][k - 4] = read_b(other, 0, k - 4);
@@ -299,21 +309,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
 #pragma unroll
   for (int g = 0; g < G_PER_STEP; ++g) issue_one(cur_t, g, 1, smem_lds + STAGE);
 
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
   int par = 0;
   for (int idx = blockIdx.x;;) {
     const int next_idx = idx + (int)gridDim.x;
     const bool has_next = next_idx < n_slots;
-    if (idx == (int)blockIdx.x) ktile(0, par, std::true_type{}, std::true_type{}, std::false_type{});
-    else ktile(0, par, std::true_type{}, std::true_type{}, std::true_type{});  // carries the end of the last read-out
+    const TileRef next_t = has_next ? tile_ref(next_idx) : cur_t;
+    if (idx == (int)blockIdx.x) ktile(0, par, I1{}, std::true_type{}, std::false_type{}, next_t, 0);
+    else ktile(0, par, I1{}, std::true_type{}, std::true_type{}, next_t, 0);  // carries the end of the last read-out
     int kt = 1;
-    for (; kt + 2 < KT; ++kt) ktile(kt, par, std::true_type{}, std::false_type{}, std::false_type{});
-    ktile(kt, par, std::false_type{}, std::false_type{}, std::false_type{});
+    for (; kt + 2 < KT; ++kt) ktile(kt, par, I1{}, std::false_type{}, std::false_type{}, next_t, 0);
+    ktile(kt, par, I2{}, std::false_type{}, std::false_type{}, next_t, has_next ? G_PER_STEP : 0);
     ++kt;
     if (!has_next) {
       final_tile(kt, par, cur_t, std::false_type{});
       break;
     }
-    const TileRef next_t = tile_ref(next_idx);
     final_tile(kt, par, next_t, std::true_type{});
     // the next tile's k-step 0 operands were read into the second register set
 #pragma unroll
