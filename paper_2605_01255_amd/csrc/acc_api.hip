@@ -256,8 +256,8 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
     const unsigned grid = gemm_bf16_plan(p, 256, 256);
     p.red_stride = (int64_t)grid * 256 * 4;
     if constexpr (sizeof(TC) == 2) {
-      if (!accumulate && grid > 256 && (int64_t)grid == (int64_t)p.tiles_m * p.tiles_n && K >= 192) {
-        // several rounds of tiles and no padding slots in the tile map: 256 persistent work-groups
+      if (!accumulate && grid > 256 && K >= 192) {
+        // several rounds of tiles: 256 persistent work-groups
         p.red_stride = (int64_t)256 * 256 * 4;
         L.launch_lds(gemm_bf16_persist_kernel<KMAJ>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)grid);
         return;

@@ -11,8 +11,7 @@
 // 128 bytes with the 16-byte chunk index XOR-ed with the row so that writes and read-backs spread over the banks).
 // The first k-step of every tile multiplies onto zero, so the accumulators are never cleared; it also carries the
 // read-out of the previous tile's last two units, which were final only after that tile's last MFMA.
-// Restrictions (the host checks them): bf16 output, no accumulation into C, no K split, every slot of the
-// XCD tile map is a real tile, K >= 192.
+// Restrictions (the host checks them): bf16 output, no accumulation into C, no K split, K >= 192.
 #pragma once
 #include "acc_gemm.h"
 
@@ -112,7 +111,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   bf16x8 af[2][TM], bfr[2][TN];
   const uint32_t smem_lds = (uint32_t)(uintptr_t)smem;
 
-  TileRef cur_t = tile_ref(blockIdx.x);
+  // slots of the XCD tile map that hold no tile (the map is padded to whole super-tiles) are skipped
+  auto next_slot = [&](int idx) -> int {
+    int tm, tn;
+    for (idx += (int)gridDim.x; idx < n_slots && !xcd_tile(p, idx, tm, tn);) idx += (int)gridDim.x;
+    return idx;
+  };
+  const int first_idx = next_slot((int)blockIdx.x - (int)gridDim.x);
+  const bool has_tile = first_idx < n_slots;
+  TileRef cur_t = tile_ref(has_tile ? first_idx : 0);
 
   // ---- read-out of a finished 32 x 64 unit (see gemm_bf16_tile) ----
   bf16* __restrict__ C = (bf16*)p.C;
@@ -283,8 +290,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   };
 
   // ---- prologue of the work-group's first tile ----
+  if (has_tile) {
 #pragma unroll
-  for (int g = 0; g < NG_TOTAL; ++g) issue_one(cur_t, g, 0, smem_lds);
+    for (int g = 0; g < NG_TOTAL; ++g) issue_one(cur_t, g, 0, smem_lds);
+  }
   if (p.red_count) {  // side job: this work-group's share of the pending partial sums (see gemm_bf16_tile)
     for (int64_t e = ((int64_t)blockIdx.x * (NW * 64) + tid) * 4; e < p.red_count; e += p.red_stride) {
       f32x4 sum = *(const f32x4*)(p.red_part + e);
@@ -300,6 +309,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
       }
     }
   }
+  if (!has_tile) return;
   wait_vmcnt0();
   __syncthreads();
 #pragma unroll
@@ -312,11 +322,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
   using I1 = std::integral_constant<int, 1>;
   using I2 = std::integral_constant<int, 2>;
   int par = 0;
-  for (int idx = blockIdx.x;;) {
-    const int next_idx = idx + (int)gridDim.x;
+  for (int idx = first_idx;;) {
+    const int next_idx = next_slot(idx);
     const bool has_next = next_idx < n_slots;
     const TileRef next_t = has_next ? tile_ref(next_idx) : cur_t;
-    if (idx == (int)blockIdx.x) ktile(0, par, I1{}, std::true_type{}, std::false_type{}, next_t, 0);
+    if (idx == first_idx) ktile(0, par, I1{}, std::true_type{}, std::false_type{}, next_t, 0);
     else ktile(0, par, I1{}, std::true_type{}, std::true_type{}, next_t, 0);  // carries the end of the last read-out
     int kt = 1;
     for (; kt + 2 < KT; ++kt) ktile(kt, par, I1{}, std::false_type{}, std::false_type{}, next_t, 0);
