@@ -184,10 +184,11 @@ def test_big_tile_gemm_with_strides(acc):
     (16384, 256, 3072, 64, (64, 8, 24)),    # four K tiles (stage parity unchanged from tile to tile), strided
     (16384, 320, 3072, 64, (0, 0, 0)),      # five K tiles (stage parity alternates)
     (16384, 3072, 3136, 64, (0, 0, 0)),     # backward: 49 K tiles, three output tiles per work-group
+    (2304, 256, 8456, 64, (0, 0, 0)),       # 9 x 34 tiles in a map of 768 slots: empty slots between a work-group's tiles
 ])
 def test_persistent_gemm_across_output_tiles(acc, n, d_in, d_out, r, pad):
-    """More than 256 output tiles of 256 x 256 without padding slots in the tile map: 256 persistent
-    work-groups whose K pipeline runs across the tile boundary (next tile requested inside the last K tile)."""
+    """More than 256 slots in the map of 256 x 256 output tiles: 256 persistent work-groups whose K pipeline
+    runs across the tile boundary (next tile requested inside the last K tiles of the one before)."""
     _check(acc, inputs.Linear(f"persist_{n}x{d_in}x{d_out}", n, d_in, d_out, r, dtype="bf16"), pad=pad)
 
 
