@@ -259,7 +259,7 @@ def main():
                 "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4),
                 "traffic": (args.traffic_mb * 1e6 if args.traffic_mb else
-                            (555.1e6 if lin.name == "c2.attn_proj" else None)),
+                            (557.2e6 if lin.name == "c2.attn_proj" else None)),
                 "algorithmic_bytes": (lin.n * lin.d_in + lin.d_in * lin.d_out + lin.n * lin.d_out) * 2}
 
     dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
