@@ -26,9 +26,7 @@ def test_c2_full_outputs(acc):
     data = inputs.make(lin)
     got = gu.run_layer(acc, lin, data)
     want = gu.run_oracle(lin, data)
-    errs = {k: gu.rel(got[k], want[k]) for k in want}
-    print(lin.name, " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
-    assert all(v <= 1e-2 for v in errs.values()), errs
+    gu.check_outputs(got, want, 1e-2, lin.name)
     # the x20 outlier channels dominate ||Xs||: check them and the ordinary channels separately
     out_ch = inputs.outlier_channels(lin.d_in, lin.n_outliers)
     rest = np.setdiff1d(np.arange(lin.d_in), out_ch)
@@ -38,22 +36,35 @@ def test_c2_full_outputs(acc):
 
 
 def _sampled_check(acc, lin, rng):
+    """Outputs the oracle can compute piece by piece: 256 random token rows of Y and dX plus three whole
+    256 x 256 output tiles of each (the first, a random one, the last: the unit a work-group writes), 64 random
+    and the last 64 channels of Xs, 64 random and the last 64 columns of Gr, and the matching block of dW.  Every
+    piece is held to the full bar (whole piece, every 32 x 32 block, every element)."""
     data = inputs.make(lin)
     got = gu.run_layer(acc, lin, data)
     X, W, dY = (inputs.as_f64(data[k]) for k in ("X", "W", "dY"))
     S = orc.sketch_matrix(lin.seed, lin.n, lin.r)
     rows = np.sort(rng.choice(lin.n, size=min(256, lin.n), replace=False))
-    chs = np.sort(rng.choice(lin.d_in, size=64, replace=False))
-    cols = np.sort(rng.choice(lin.d_out, size=64, replace=False))
+    chs = np.union1d(rng.choice(lin.d_in - 64, size=64, replace=False), np.arange(lin.d_in - 64, lin.d_in))
+    cols = np.union1d(rng.choice(lin.d_out - 64, size=64, replace=False), np.arange(lin.d_out - 64, lin.d_out))
     Y_rows, _ = orc.linear_fwd(X[rows], W, S=S[rows])
     dX_rows, _, _ = orc.linear_bwd(dY[rows], W, np.zeros((lin.d_in, lin.r)), S=S[rows], want_dW=False)
-    _, Xs_ch = orc.linear_fwd(X[:, chs], W[chs][:, :8], S=S)                       # [64, r]
-    _, Gr_cols, dW_blk = orc.linear_bwd(dY[:, cols], W[:8][:, cols], Xs_ch, S=S)   # [r, 64], [64, 64]
-    errs = {"Y": gu.rel(got["Y"][rows], Y_rows), "dX": gu.rel(got["dX"][rows], dX_rows),
-            "Xs": gu.rel(got["Xs"][chs], Xs_ch), "Gr": gu.rel(got["Gr"][:, cols], Gr_cols),
-            "dW": gu.rel(got["dW"][np.ix_(chs, cols)], dW_blk)}
-    print(lin.name, f"r={lin.r}", " ".join(f"{k}={v:.2e}" for k, v in errs.items()), flush=True)
-    assert all(v <= 1e-2 for v in errs.values()), (lin.name, errs)
+    _, Xs_ch = orc.linear_fwd(X[:, chs], W[chs][:, :8], S=S)                       # [128, r]
+    _, Gr_cols, dW_blk = orc.linear_bwd(dY[:, cols], W[:8][:, cols], Xs_ch, S=S)   # [r, 128], [128, 128]
+    have = {"Y": got["Y"][rows], "dX": got["dX"][rows], "Xs": got["Xs"][chs], "Gr": got["Gr"][:, cols],
+            "dW": got["dW"][np.ix_(chs, cols)]}
+    want = {"Y": Y_rows, "dX": dX_rows, "Xs": Xs_ch, "Gr": Gr_cols, "dW": dW_blk}
+
+    def tile_slices(extent_m, extent_n):
+        tm, tn = -(-extent_m // 256), -(-extent_n // 256)
+        picks = {(0, 0), (int(rng.integers(tm)), int(rng.integers(tn))), (tm - 1, tn - 1)}
+        return [(slice(a * 256, min(extent_m, a * 256 + 256)), slice(b * 256, min(extent_n, b * 256 + 256)))
+                for a, b in sorted(picks)]
+    for i, (rs, cs) in enumerate(tile_slices(lin.n, lin.d_out)):
+        have[f"Y.tile{i}"], want[f"Y.tile{i}"] = got["Y"][rs, cs], X[rs] @ W[:, cs]
+    for i, (rs, cs) in enumerate(tile_slices(lin.n, lin.d_in)):
+        have[f"dX.tile{i}"], want[f"dX.tile{i}"] = got["dX"][rs, cs], dY[rs] @ W[cs].T
+    gu.check_outputs(have, want, 1e-2, f"{lin.name} r={lin.r}")
     # invariants that hold at any size: S^T S structure shows up as ||Gr||^2 ~ ||dY||^2 (1/r per column pair)
     ratio = np.sum(got["Gr"] ** 2) / np.sum(dY ** 2)
     assert 0.9 < ratio < 1.1, ratio
@@ -73,9 +84,17 @@ def test_c3_down_ranks_sampled(acc, r):
     _sampled_check(acc, lin, np.random.default_rng(2))
 
 
-@pytest.mark.parametrize("name", ["c5.q", "c5.k"])
+@pytest.mark.parametrize("r", [64, 512])
+def test_c3_gate_ranks_sampled(acc, r):
+    """MLP gate projection (3072 -> 8192) at the ends of the rank sweep."""
+    lin = [l for l in inputs.config(f"c3_r{r}") if l.name == "c3.gate"][0]
+    _sampled_check(acc, lin, np.random.default_rng(6))
+
+
+@pytest.mark.parametrize("name", ["c5.q", "c5.k", "c5.gate", "c5.down"])
 def test_c5_linears_sampled(acc, name):
-    """8B-shaped layer, n = 65536 tokens, r = 512, low-rank-plus-noise activations."""
+    """8B-shaped layer, n = 65536 tokens, r = 512, low-rank-plus-noise activations; the MLP linears have an
+    intermediate width of 14336 (the down projection's input is 1.88 GB)."""
     lin = [l for l in inputs.config("c5") if l.name == name][0]
     _sampled_check(acc, lin, np.random.default_rng(3))
 

@@ -68,3 +68,54 @@ def test_sketch_matrix_bf16_generator(acc, n, r):
     assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 3e-6 / np.sqrt(r))
     rounded = orc.round_to_bf16(want)
     assert np.mean(rounded != got) < 2e-3                        # nearly always the same bf16 value
+
+
+def _identity_like(acc, n, d):
+    """[n, d] bf16 device matrix with ones on the main diagonal (d >= n)."""
+    import torch
+    m = torch.zeros(n, d, dtype=torch.bfloat16, device="cuda:0")
+    m[torch.arange(n), torch.arange(n)] = 1.0
+    return m
+
+
+@pytest.mark.parametrize("n,d,r,row_offset,one_launch", [
+    (512, 512, 64, 0, False),                      # one channel slab, one column slice, two token splits
+    (512, 512, 256, 0, False),                     # four column slices
+    (1030, 1088, 64, 4 * 33, False),               # ragged token count (not even a multiple of 4), ragged slab
+    (1030, 1088, 256, 0, False),
+    (1030, 1032, 48, 0, False),                    # rank below the tile's 64 columns (surplus columns masked)
+    (1024, 1024, 128, 0, True),                    # the 512 x 128 tile
+    (1024, 1024, 256, 8, True),
+    (1024, 1024, 64, (1 << 34) - 512, False),      # token indices crossing 2^34 inside the range
+    (1024, 1024, 128, (1 << 34) - 512, True),
+    (8192, 8192, 256, 0, False),                   # 16 channel slabs, 2048 tokens (64 stages) per split
+    (4096, 4096, 512, 4096, True),                 # eight column slices of the narrow tile's width, wide tile
+])
+def test_layer_kernels_regenerate_s_entry_by_entry(acc, n, d, r, row_offset, one_launch):
+    """The sketch kernels' own generator (their Philox rounds, counter arithmetic, Box-Muller and the exchange of
+    generated pieces between waves), pinned through the layer calls: with X = I the forward's factor is
+    Xs = X^T.S = S itself, with dY = I the backward's factor is Gr = S^T, each product having one non-zero term,
+    so every entry of the factors is one entry of S as the kernel generated and rounded it."""
+    import torch
+    seed = 0xC0FFEE123456789
+    flags = acc.ACC_FLAG_ONE_LAUNCH if one_launch else 0
+    desc = acc.make_desc(n, d, d, r, seed=seed, io_dtype=acc.ACC_BF16, row_offset=row_offset, flags=flags)
+    eye = _identity_like(acc, n, d)
+    W = torch.zeros(d, d, dtype=torch.bfloat16, device="cuda:0")
+    Y = torch.empty(n, d, dtype=torch.bfloat16, device="cuda:0")
+    dX = torch.empty(n, d, dtype=torch.bfloat16, device="cuda:0")
+    Xs = torch.full((d, r), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    Gr = torch.full((r, d), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    acc.acc_linear_fwd(desc, eye, W, Y, Xs, acc.alloc_workspace(desc, False))
+    acc.acc_linear_bwd(desc, eye, W, Xs, dX, Gr, None, acc.alloc_workspace(desc, True))
+    torch.cuda.synchronize()
+    want = orc.sketch_matrix(seed, n, r, row_offset)
+    rounded = orc.round_to_bf16(want)
+    for name, got in (("Xs", acc.to_host_f64(Xs)), ("Gr", acc.to_host_f64(Gr).T)):
+        assert np.all(got[n:] == 0.0), name                          # channels no token touches
+        got = got[:n]
+        # hardware log / sqrt / sin / cos against libm: a few 1e-6 of 1/sqrt(r) before the rounding to bf16
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 3e-6 / np.sqrt(r)), name
+        mismatch = float(np.mean(rounded != got))
+        print(name, n, r, "fraction of entries one bf16 step off:", mismatch, flush=True)
+        assert mismatch < 2e-3, (name, mismatch)                     # nearly always the very same bf16 value
