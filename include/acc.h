@@ -110,6 +110,20 @@ size_t acc_linear_workspace_bytes(const acc_linear_desc* desc, int is_backward);
 int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
                    void* workspace, size_t ws_bytes, void* stream);
 
+/* acc_linear_fwd for callers that cannot allocate or pass a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, kernels and results, but the split-token
+ * partial tiles of the sketch go to a static device array inside the library, ACC_STATIC_SCRATCH_BYTES
+ * (32 MiB) per GPU, held until the process ends.  The call allocates nothing.  A descriptor whose
+ * acc_linear_workspace_bytes(desc, 0) exceeds that size returns ACC_ERR_WORKSPACE and launches nothing (the
+ * 3B-shaped projection at r = 256 needs 31.5 MB and fits; with ACC_FLAG_SKIP_SKETCH nothing is needed).
+ * All calls on one GPU share the array: calls that may overlap there (different streams without an event
+ * between them, several host threads) race on it; order them, or use acc_linear_fwd with workspaces of
+ * their own.  Nothing in the array has to be cleared between calls: every partial a call reads it has
+ * written before. */
+#define ACC_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int acc_linear_fwd_static(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
+                          void* stream);
+
 /* Backward (Def. 3.1 and Thm 3.2.2(a): dX = dY.W^T is exact; Sec. 4: the weight gradient is
  * kept as two rank-r factors).  Computes dX [n, ldx], Gr = S^T.dY [r, d_out] (dense) and, when
  * dW != NULL, the dense dW = Xs.Gr [d_in, d_out] (Sec. 4, update strategy (i)).

@@ -19,7 +19,10 @@ ACC_FLAG_W_OUT_IN = 4
 ACC_FLAG_DW_ACCUMULATE = 8
 ACC_FLAG_RSVD_POWER_SHIFT = 8   # flags bits 8..9: rounds of subspace iteration of the RSVD forward
 
-EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_bwd", "acc_linear_bias_grad",
+ACC_STATIC_SCRATCH_BYTES = 32 << 20
+
+EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_fwd_static", "acc_linear_bwd",
+           "acc_linear_bias_grad",
            "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_lowrank_workspace_bytes",
            "acc_lowrank_projector", "acc_lowrank_adamw_step",
            "acc_philox_dump_u32",
@@ -62,6 +65,8 @@ _lib.acc_linear_workspace_bytes.restype = _sz
 _lib.acc_linear_workspace_bytes.argtypes = [_dp, ctypes.c_int]
 _lib.acc_linear_fwd.restype = ctypes.c_int
 _lib.acc_linear_fwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_fwd_static.restype = ctypes.c_int
+_lib.acc_linear_fwd_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 _lib.acc_linear_bwd.restype = ctypes.c_int
 _lib.acc_linear_bwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_linear_bias_grad.restype = ctypes.c_int
@@ -140,6 +145,11 @@ def acc_linear_fwd(desc, X, W, Y, Xs, workspace, stream=None, ws_bytes=None):
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.acc_linear_fwd(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(Y), _ptr(Xs),
                                _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_fwd_static(desc, X, W, Y, Xs, stream=None):
+    """acc_linear_fwd with the partial tiles in the library's static device array (nothing is allocated)."""
+    _check(_lib.acc_linear_fwd_static(ctypes.byref(desc), _ptr(X), _ptr(W), _ptr(Y), _ptr(Xs), _stream(stream)))
 
 
 def acc_linear_bwd(desc, dY, W, Xs, dX, Gr, dW, workspace, stream=None, ws_bytes=None):

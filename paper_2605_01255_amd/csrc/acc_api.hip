@@ -19,10 +19,17 @@
 #include "acc_sketch.h"
 #include "acc_gemm_persist.h"
 
+// Scratch of acc_linear_fwd_static (the entry point for callers that cannot allocate): the split-token partial
+// tiles of the sketch live here instead of in a caller's workspace.  Every GPU the library runs on holds its own
+// copy of the array until the process ends.  In host code the name is only a handle for hipGetSymbolAddress;
+// kernels get the device address looked up once per device (static_scratch()).
+constexpr size_t kStaticScratchBytes = ACC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace acc {
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 101;  // 0.1.1
 
 bool valid_dtype(int32_t d) { return d == ACC_F32 || d == ACC_BF16; }
 size_t dtype_size(int32_t d) { return d == ACC_BF16 ? 2 : 4; }
@@ -715,6 +722,44 @@ size_t workspace_bytes(const acc_linear_desc* d, const Shape& s, bool backward) 
   return (size_t)sp.G * (size_t)channels * (size_t)s.r * sizeof(float);
 }
 
+// Device address of this device's copy of `scratch`, looked up on the first call with that device current.
+int static_scratch(float** out) {
+  static void* ptr[64];
+  static std::mutex mu;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= 64) return ACC_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    ptr[dev] = p;
+  }
+  *out = (float*)ptr[dev];
+  return ACC_OK;
+}
+
+// Enqueues the forward pass; every argument has been validated.
+int enqueue_forward(const acc_linear_desc* desc, const Shape& s, const void* X, const void* W, void* Y, void* Xs,
+                    float* workspace, hipStream_t stream) {
+  const bool sketch = !(desc->flags & ACC_FLAG_SKIP_SKETCH);
+  Launcher L{stream};
+  const SketchPlan sp_f = plan_sketch(desc, s.n, s.d_in, s.ldx);
+  if (sketch && fused_ok(desc, sp_f, s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
+    fused_pass<false, false>(desc, sp_f, X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, Xs, workspace, L);
+    return L.status();
+  }
+  // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
+  // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
+  ReduceJob job{};  // with a tuned GEMM next, the sketch leaves its K4 reduction to that launch
+  if (sketch)
+    run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, workspace, L, forward_gemm_is_tuned(desc, s) ? &job : nullptr);
+  exact_forward_gemm(desc, s, X, W, Y, L, &job);
+  return L.status();
+}
+
 }  // namespace
 }  // namespace acc
 
@@ -739,21 +784,22 @@ int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, vo
     return ACC_ERR_ALIGN;
   if (sketch && (!workspace || ws_bytes < workspace_bytes(desc, s, false))) return ACC_ERR_WORKSPACE;
   if ((rc = check_device()) != ACC_OK) return rc;
-  Launcher L{(hipStream_t)stream};
+  return enqueue_forward(desc, s, X, W, Y, Xs, (float*)workspace, (hipStream_t)stream);
+}
 
-  const SketchPlan sp_f = plan_sketch(desc, s.n, s.d_in, s.ldx);
-  if (sketch && fused_ok(desc, sp_f, s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
-    fused_pass<false, false>(desc, sp_f, X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, Xs, (float*)workspace, L);
-    return L.status();
-  }
-  // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
-  // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
-  ReduceJob job{};  // with a tuned GEMM next, the sketch leaves its K4 reduction to that launch
-  if (sketch)
-    run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, (float*)workspace, L,
-               forward_gemm_is_tuned(desc, s) ? &job : nullptr);
-  exact_forward_gemm(desc, s, X, W, Y, L, &job);
-  return L.status();
+int acc_linear_fwd_static(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
+                          void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  const bool sketch = !(desc->flags & ACC_FLAG_SKIP_SKETCH);
+  if (!X || !W || !Y || (sketch && !Xs)) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(X) || !aligned16(W) || !aligned16(Y) || !aligned16(Xs)) return ACC_ERR_ALIGN;
+  if (sketch && workspace_bytes(desc, s, false) > kStaticScratchBytes) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  float* ws = nullptr;
+  if ((rc = static_scratch(&ws)) != ACC_OK) return rc;
+  return enqueue_forward(desc, s, X, W, Y, Xs, ws, (hipStream_t)stream);
 }
 
 int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, const void* Xs,
