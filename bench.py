@@ -35,8 +35,21 @@ def parse():
                     help="also run a plain 256 MiB device copy 5 times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--traffic-mb", type=float, default=None,
                     help="HBM-side MB per launch of the dominant kernel, from rocprofv3 --pmc runs; default: the figure "
-                         "measured for the default workload (profiles/c2_attn_proj_counters.md), null for others")
+                         "stored beside the counter summary of this workload under profiles/, null if there is none")
     return ap.parse_args()
+
+
+def stored_traffic(workload):
+    """HBM-side bytes per launch of the dominant kernel for `workload`, as measured with rocprofv3 --pmc and
+    recorded beside the counter summary (a line `traffic_bytes_per_launch[<workload>] = <bytes>` in
+    profiles/*_counters.md); None when no profile of this workload is stored."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*counters*.md"))):
+        m = re.search(r"traffic_bytes_per_launch\[" + re.escape(workload) + r"\]\s*=\s*([0-9.eE+]+)", open(path).read())
+        if m:
+            return float(m.group(1))
+    return None
 
 
 class Buffers:
@@ -216,73 +229,15 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-
+    # Order of the legs: single steps and the rows beside the headline run first, then the headline region
+    # (warm-up, timed steps), then the per-phase and single-kernel timings.  The part raises its clocks over the
+    # first 20-30 ms of load after idling (measured: single steps 0.77, 0.75, 0.72, ... 0.60 ms when the region
+    # starts 3 ms after idle, 0.58 ms once settled), and host-side input generation leaves it idle for seconds,
+    # so a region that came first with a short warm-up would time that ramp; `timed_region` shows the single
+    # steps of the region either way.
     flops = lin.flops(with_dw)
-    value = flops / (ms_per_step * 1e-3) / 1e12
-    peak = PEAK_BF16_TFLOPS if lin.dtype == "bf16" else PEAK_F32_TFLOPS
-
+    step(0)
     step_median, step_min = time_each(torch, step, args.steps)
-    # per-phase event timings (same launches, HIP events on the launch stream)
-    ms_fwd = time_events(torch, fwd, args.steps)
-    ms_bwd = time_events(torch, bwd, args.steps)
-    # the same step with the weight gradient left in factored form (no dense dW)
-    ms_bwd_nodw = None
-    if with_dw:
-        def bwd_nodw(i):
-            b = sets[i % len(sets)]
-            acc.acc_linear_bwd(desc, b.dY, b.W, b.Xs, b.dX, b.Gr, None, ws_b)
-        bwd_nodw(0)
-        ms_bwd_nodw = time_events(torch, bwd_nodw, args.steps)
-    # dominant kernel: the exact-output GEMM Y = X.W, launched alone by a forward with the
-    # sketch skipped (that call enqueues exactly one kernel)
-    desc_gemm = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code,
-                              flags=acc.ACC_FLAG_SKIP_SKETCH)
-
-    def gemm_only(i):
-        b = sets[i % len(sets)]
-        acc.acc_linear_fwd(desc_gemm, b.X, b.W, b.Y, None, None)
-
-    gemm_only(0)
-    ms_gemm = time_events(torch, gemm_only, args.steps)
-    gemm_flops = 2 * lin.n * lin.d_in * lin.d_out
-    achieved = gemm_flops / (ms_gemm * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "Y = X.W GEMM (acc_linear_fwd, sketch skipped)",
-                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4),
-                "traffic": (args.traffic_mb * 1e6 if args.traffic_mb else
-                            (557.2e6 if lin.name == "c2.attn_proj" else None)),
-                "algorithmic_bytes": (lin.n * lin.d_in + lin.d_in * lin.d_out + lin.n * lin.d_out) * 2}
-
-    dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
-    out = {
-        "metric": "compressed-linear fwd+bwd TFLOP/s", "value": round(value, 2), "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{lin.name}: n={lin.n} tokens, {lin.d_in}->{lin.d_out}, r={lin.r}, "
-                               f"{lin.dtype}, X with {lin.n_outliers} outlier channels x20"
-                               if lin.x_kind == "outlier" else f"{lin.name}: n={lin.n}, {lin.d_in}->{lin.d_out}, r={lin.r}, {lin.dtype}",
-                   "with_dw": with_dw, "buffer_sets": len(sets)},
-        "pct_of_bf16_mfma_peak": round(100.0 * value / peak, 2),
-        "ms_per_step_median": round(step_median, 4), "ms_per_step_min": round(step_min, 4),
-        "ms_fwd": round(ms_fwd, 4), "ms_bwd": round(ms_bwd, 4),
-        "factored_only": None if ms_bwd_nodw is None else {
-            "ms_bwd": round(ms_bwd_nodw, 4),
-            "value": round(lin.flops(False) / ((ms_fwd + ms_bwd_nodw) * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},
-        "activation_bytes_per_token": {"dense": dense_b / lin.n, "kept": round(kept_b / lin.n, 4),
-                                       "saved": round((dense_b - kept_b) / lin.n, 4),
-                                       "ratio": round(dense_b / kept_b, 2)},
-        "roofline": roofline,
-    }
     # rows added after the hot path: bias gradient (HBM-bound column sum of dY) and the layer with W in
     # the [d_out, d_in] orientation; reported beside the headline, not part of `value`
     tdt = acc.torch_dtype(code)
@@ -367,7 +322,7 @@ def main():
     ms_optk = time_events(torch, opt_step_projected, args.steps)
     ms_optr = time_events(torch, opt_step_left, args.steps)
     w_bytes = 2 * lin.d_in * lin.d_out * (2 if lin.dtype == "bf16" else 4)   # W read and written once
-    out["widened"] = {
+    widened = {
         "lowrank_adamw": {"projector_rank": k_opt, "ms_step_projected": round(ms_optk, 4),
                           "ms_step_left_factor_as_projector": round(ms_optr, 4),
                           "ms_projector_refresh": round(ms_proj, 4), "bound": "hbm",
@@ -380,6 +335,89 @@ def main():
         "bias_grad": {"ms": round(ms_db, 4), "bound": "hbm", "achieved": round(db_bytes / (ms_db * 1e-3) / 1e9, 1),
                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(db_bytes / (ms_db * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
         "w_out_in": {"ms_per_step": round(ms_oi, 4), "value": round(flops / (ms_oi * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},
+    }
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # The timed region: exactly args.steps steps between two synchronisations, host clock.  One HIP event after
+    # every step (on the launch stream; recording costs about a microsecond of host time and nothing on the GPU)
+    # shows afterwards where inside the region the time went.
+    st = torch.cuda.current_stream()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    marks[0].record(st)
+    for i in range(args.steps):
+        step(i)
+        marks[i + 1].record(st)
+    t_enqueued = time.perf_counter()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+    timed_region = {
+        "wall_ms": round(wall * 1e3, 4), "host_enqueue_ms": round((t_enqueued - t0) * 1e3, 4),
+        "first_to_last_event_ms": round(marks[0].elapsed_time(marks[-1]), 4),
+        "step_ms_first5": [round(t, 4) for t in per_step[:5]],
+        "step_ms_last5": [round(t, 4) for t in per_step[-5:]],
+        "step_ms_median": round(sorted(per_step)[len(per_step) // 2], 4)}
+
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if lin.dtype == "bf16" else PEAK_F32_TFLOPS
+
+    # per-phase event timings (same launches, HIP events on the launch stream)
+    for i in range(len(sets)):             # every buffer set holds an Xs before a backward leg reads it
+        fwd(i)
+    ms_fwd = time_events(torch, fwd, args.steps)
+    ms_bwd = time_events(torch, bwd, args.steps)
+    # the same step with the weight gradient left in factored form (no dense dW)
+    ms_bwd_nodw = None
+    if with_dw:
+        def bwd_nodw(i):
+            b = sets[i % len(sets)]
+            acc.acc_linear_bwd(desc, b.dY, b.W, b.Xs, b.dX, b.Gr, None, ws_b)
+        bwd_nodw(0)
+        ms_bwd_nodw = time_events(torch, bwd_nodw, args.steps)
+    # dominant kernel: the exact-output GEMM Y = X.W, launched alone by a forward with the
+    # sketch skipped (that call enqueues exactly one kernel)
+    desc_gemm = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, io_dtype=code,
+                              flags=acc.ACC_FLAG_SKIP_SKETCH)
+
+    def gemm_only(i):
+        b = sets[i % len(sets)]
+        acc.acc_linear_fwd(desc_gemm, b.X, b.W, b.Y, None, None)
+
+    gemm_only(0)
+    ms_gemm = time_events(torch, gemm_only, args.steps)
+    gemm_flops = 2 * lin.n * lin.d_in * lin.d_out
+    achieved = gemm_flops / (ms_gemm * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "Y = X.W GEMM (acc_linear_fwd, sketch skipped)",
+                "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "avg_kernel_ms": round(ms_gemm, 4),
+                "traffic": args.traffic_mb * 1e6 if args.traffic_mb else stored_traffic(lin.name),
+                "algorithmic_bytes": (lin.n * lin.d_in + lin.d_in * lin.d_out + lin.n * lin.d_out) * 2}
+
+    dense_b, kept_b = lin.activation_bytes(2 if lin.dtype == "bf16" else 4)
+    out = {
+        "metric": "compressed-linear fwd+bwd TFLOP/s", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{lin.name}: n={lin.n} tokens, {lin.d_in}->{lin.d_out}, r={lin.r}, "
+                               f"{lin.dtype}, X with {lin.n_outliers} outlier channels x20"
+                               if lin.x_kind == "outlier" else f"{lin.name}: n={lin.n}, {lin.d_in}->{lin.d_out}, r={lin.r}, {lin.dtype}",
+                   "with_dw": with_dw, "buffer_sets": len(sets)},
+        "pct_of_bf16_mfma_peak": round(100.0 * value / peak, 2),
+        "ms_per_step_median": round(step_median, 4), "ms_per_step_min": round(step_min, 4),
+        "timed_region": timed_region,
+        "ms_fwd": round(ms_fwd, 4), "ms_bwd": round(ms_bwd, 4),
+        "factored_only": None if ms_bwd_nodw is None else {
+            "ms_bwd": round(ms_bwd_nodw, 4),
+            "value": round(lin.flops(False) / ((ms_fwd + ms_bwd_nodw) * 1e-3) / 1e12, 2), "unit": "TFLOP/s"},
+        "activation_bytes_per_token": {"dense": dense_b / lin.n, "kept": round(kept_b / lin.n, 4),
+                                       "saved": round((dense_b - kept_b) / lin.n, 4),
+                                       "ratio": round(dense_b / kept_b, 2)},
+        "roofline": roofline,
+        "widened": widened,
     }
     if not args.no_cpu_baseline:
         # the whole 3B-shaped projection is ~1-2 s of fp64 BLAS on the machine's cores; larger shapes are sampled

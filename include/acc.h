@@ -221,9 +221,12 @@ int acc_linear_bwd_rsvd(const acc_linear_desc* desc, const void* dY, const void*
 int acc_philox_dump_u32(uint64_t seed, uint64_t row_offset, int64_t n, int64_t r, uint32_t* out,
                         void* stream);
 
-/* Test hook: S itself as float32 [n, r] (device), produced by the same device code the layer
- * kernels use: io_dtype ACC_F32 gives the fp32 generator, ACC_BF16 the fast generator rounded
- * to bfloat16 and widened.  Only n, r, seed, row_offset and io_dtype of desc are read. */
+/* Test hook: S itself as float32 [n, r] (device).  io_dtype ACC_F32 gives the fp32 generator of the generic
+ * kernels (libm-grade log / sincos); ACC_BF16 the hardware-transcendental Box-Muller of the bf16 kernels,
+ * rounded to bfloat16 and widened.  The hook runs the straightforward form of that arithmetic (one call per
+ * lane, acc_rng.h); the tuned sketch kernels carry their own interleaved copy with its own counter
+ * arithmetic, which is pinned separately by running the layer calls on identity inputs (X = I gives Xs = S).
+ * Only n, r, seed, row_offset and io_dtype of desc are read. */
 int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream);
 
 /* Human-readable name of a status code (static string, never NULL). */

@@ -218,3 +218,23 @@ def test_hyperparameter_struct_matches_header():
     for typ, names in re.findall(r"\b(float|int32_t)\s+([\w\s,]+);", body):
         fields += [(n.strip(), ctypes.c_float if typ == "float" else ctypes.c_int32) for n in names.split(",")]
     assert fields == list(acc.AccAdamwHyper._fields_)
+
+
+def test_static_scratch_forward_validates_before_it_touches_a_device():
+    f = acc._lib.acc_linear_fwd_static
+    args = (0x1000, 0x2000, 0x3000, 0x4000, None)
+    assert f(None, *args) == -1
+    d = acc.make_desc(256, 256, 512, 16, io_dtype=acc.ACC_F32)
+    assert f(ctypes.byref(d), 0, 0x2000, 0x3000, 0x4000, None) == -1
+    assert f(ctypes.byref(d), 0x1004, 0x2000, 0x3000, 0x4000, None) == -3
+    assert f(ctypes.byref(acc.make_desc(256, 256, 512, 20)), *args) == -2
+    # partial tiles beyond the static array: refused, nothing launched
+    big = acc.make_desc(65536, 4096, 4096, 512)
+    assert acc.acc_linear_workspace_bytes(big, False) > acc.ACC_STATIC_SCRATCH_BYTES
+    assert f(ctypes.byref(big), *args) == -5
+    # with the sketch skipped no scratch is needed at all
+    skip = acc.make_desc(65536, 4096, 4096, 512, flags=acc.ACC_FLAG_SKIP_SKETCH)
+    assert f(ctypes.byref(skip), 0x1000, 0x2000, 0x3000, None, None) in (0, -6)
+    header = open(HEADER).read()
+    assert re.search(r"#define ACC_STATIC_SCRATCH_BYTES \(\(size_t\)32 << 20\)", header)
+    assert acc.ACC_STATIC_SCRATCH_BYTES == 32 << 20
