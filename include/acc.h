@@ -51,7 +51,7 @@ enum {
   ACC_ERR_INVALID_ARG = -1, /* NULL descriptor or required pointer, unknown flag            */
   ACC_ERR_SHAPE = -2,       /* a size is <= 0 or above its limit (n <= 2^30, d_in, d_out <= 2^21,
                                r <= 2^16), r % 8 != 0, d_in % 8 or d_out % 8 != 0,
-                               a row stride smaller than the row or not a multiple of 8,
+                               a row stride (ldx, ldw, ldy, ldf) smaller than the row or not a multiple of 8,
                                row_offset % 4 != 0                                           */
   ACC_ERR_ALIGN = -3,       /* a pointer is not 16-byte aligned                              */
   ACC_ERR_DTYPE = -4,       /* a dtype field is not ACC_F32 / ACC_BF16                       */
@@ -96,6 +96,10 @@ typedef struct acc_linear_desc {
   int32_t factor_dtype; /* acc_dtype of Xs and Gr                                            */
   int32_t dw_dtype;     /* acc_dtype of the dense dW (ignored when dW == NULL)               */
   uint32_t flags;       /* ACC_FLAG_*                                                        */
+  int64_t ldf;          /* row stride, in elements, of the factors whose rows hold r elements: Xs
+                           [d_in, r] and, under ACC_FLAG_W_OUT_IN, Gr [d_out, r]; 0 = r (dense);
+                           otherwise >= r and a multiple of 8.  Lets a call write its factor into a
+                           column block of a wider matrix (stacked factors, see acc_linear_dw).      */
 } acc_linear_desc;
 
 /* Bytes of device workspace the forward (is_backward == 0) or backward call needs for the
@@ -105,7 +109,7 @@ size_t acc_linear_workspace_bytes(const acc_linear_desc* desc, int is_backward);
 /* Forward of the compressed linear operator (Def. 3.1: the output is exact, the input is
  * compressed and stored; Sec. 4: the stored factor).  Computes Y = X.W and, unless
  * ACC_FLAG_SKIP_SKETCH is set, Xs = X^T.S with S regenerated from (seed, row_offset).
- * X [n, ldx], W [d_in, ldw] are read; Y [n, ldy] and Xs [d_in, r] (dense) are overwritten.
+ * X [n, ldx], W [d_in, ldw] are read; Y [n, ldy] and Xs [d_in, ldf] (columns 0 .. r-1 of each row) are overwritten.
  * workspace: ws_bytes >= acc_linear_workspace_bytes(desc, 0); contents are scratch. */
 int acc_linear_fwd(const acc_linear_desc* desc, const void* X, const void* W, void* Y, void* Xs,
                    void* workspace, size_t ws_bytes, void* stream);
@@ -131,6 +135,20 @@ int acc_linear_fwd_static(const acc_linear_desc* desc, const void* X, const void
  * are read.  Xs may be NULL when dW is NULL. */
 int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, const void* Xs,
                    void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes, void* stream);
+
+/* The dense weight gradient from the two factors alone (Sec. 4, update strategy (i): full-gradient
+ * reconstruction), as a call of its own: dW [d_in, d_out] = Xs.Gr, or += with ACC_FLAG_DW_ACCUMULATE (under
+ * ACC_FLAG_W_OUT_IN dW [d_out, d_in] = Gr.Xs^T).  Xs [d_in, ldf] and Gr ([r, d_out] dense, or [d_out, ldf]) of
+ * factor_dtype are read; only d_in, d_out, r, ldf, factor_dtype, dw_dtype and those two flags of desc matter (n
+ * must be valid).  No workspace.
+ * Accumulation over micro-batches WITHOUT a dense gradient (the paper stops at one batch; the factored form
+ * adds up by stacking): micro-batch m of M runs acc_linear_fwd / acc_linear_bwd with rank r, ldf = M r, Xs
+ * pointing at column m r of a stacked left factor [d_in, M r], Gr at row m r of a stacked small factor
+ * [M r, d_out] (column m r of [d_out, M r] under ACC_FLAG_W_OUT_IN), dW = NULL, and a row_offset (or seed) of
+ * its own so that the batches draw independent rows of S.  Then sum_m Xs_m.Gr_m = Xs_stack.Gr_stack exactly: the
+ * stacked pair is a rank-M r factored gradient that acc_linear_dw (r := M r, ldf = 0), acc_lowrank_projector and
+ * acc_lowrank_adamw_step take like any other; 2 M r (d_in + d_out) bytes are held instead of d_in d_out. */
+int acc_linear_dw(const acc_linear_desc* desc, const void* Xs, const void* Gr, void* dW, void* stream);
 
 /* Gradient of a bias b [d_out] that is broadcast over tokens (proof of Thm 3.2.2, bias term: the
  * gradient of the added term is grad_Z L itself, independent of X, hence exact under compression):
@@ -169,7 +187,8 @@ typedef struct acc_adamw_hyper {
 
 /* Bytes of device workspace of acc_lowrank_adamw_step and acc_lowrank_projector for projector rank k (k == 0:
  * the step without a projector); 0 = invalid descriptor or k.  Of desc only d_in, d_out, r, ldw, io_dtype,
- * factor_dtype, seed and ACC_FLAG_W_OUT_IN matter to the three calls (n must be valid; it is not used). */
+ * factor_dtype, seed and ACC_FLAG_W_OUT_IN matter to the three calls (n must be valid; it is not used; the
+ * factors are dense: ldf must be 0 or r). */
 size_t acc_lowrank_workspace_bytes(const acc_linear_desc* desc, int64_t k);
 
 /* P [d_in, k] (dense, factor_dtype) is overwritten with the projector of the factored gradient left . Gr.
@@ -196,7 +215,7 @@ int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* h
  * final rotation to singular vectors, subspace iterations only on request (ACC_FLAG_RSVD_POWER_*):
  *   Omega [d_in, r] Gaussian, Omega[c, j] = the Philox normal of (seed, token index := c, column j);
  *   Yr = X.Omega;  Yr = U.R, U^T.U = I, diag(R) > 0 (Cholesky QR, applied twice);  V = X^T.U.
- * Here desc->r is the rank: multiple of 8, 8 <= r <= 64, r <= n, r <= d_in (else ACC_ERR_SHAPE);
+ * Here desc->r is the rank: multiple of 8, 8 <= r <= 64, r <= n, r <= d_in, ldf 0 or r (else ACC_ERR_SHAPE);
  * row_offset is ignored; ACC_FLAG_SKIP_SKETCH and ACC_FLAG_ONE_LAUNCH are refused.  If Yr has
  * dependent columns (rank(X) < r) the corresponding columns of U and V are zero; U.V^T is still the
  * projection of X onto the range of Yr.  U and V are stored as factor_dtype.                        */

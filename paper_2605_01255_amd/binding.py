@@ -21,7 +21,7 @@ ACC_FLAG_RSVD_POWER_SHIFT = 8   # flags bits 8..9: rounds of subspace iteration 
 
 ACC_STATIC_SCRATCH_BYTES = 32 << 20
 
-EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_fwd_static", "acc_linear_bwd",
+EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_fwd_static", "acc_linear_bwd", "acc_linear_dw",
            "acc_linear_bias_grad",
            "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_lowrank_workspace_bytes",
            "acc_lowrank_projector", "acc_lowrank_adamw_step",
@@ -35,7 +35,7 @@ class AccLinearDesc(ctypes.Structure):
                 ("r", ctypes.c_int64), ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64),
                 ("ldy", ctypes.c_int64), ("seed", ctypes.c_uint64), ("row_offset", ctypes.c_uint64),
                 ("io_dtype", ctypes.c_int32), ("factor_dtype", ctypes.c_int32),
-                ("dw_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+                ("dw_dtype", ctypes.c_int32), ("flags", ctypes.c_uint32), ("ldf", ctypes.c_int64)]
 
 
 class AccAdamwHyper(ctypes.Structure):
@@ -69,6 +69,8 @@ _lib.acc_linear_fwd_static.restype = ctypes.c_int
 _lib.acc_linear_fwd_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 _lib.acc_linear_bwd.restype = ctypes.c_int
 _lib.acc_linear_bwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_dw.restype = ctypes.c_int
+_lib.acc_linear_dw.argtypes = [_dp, _vp, _vp, _vp, _vp]
 _lib.acc_linear_bias_grad.restype = ctypes.c_int
 _lib.acc_linear_bias_grad.argtypes = [_dp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_rsvd_workspace_bytes.restype = _sz
@@ -103,13 +105,13 @@ def acc_version() -> int:
 
 
 def make_desc(n, d_in, d_out, r, seed=0, io_dtype=ACC_BF16, factor_dtype=None, dw_dtype=None,
-              row_offset=0, ldx=0, ldw=0, ldy=0, flags=0) -> AccLinearDesc:
+              row_offset=0, ldx=0, ldw=0, ldy=0, flags=0, ldf=0) -> AccLinearDesc:
     if factor_dtype is None:
         factor_dtype = io_dtype
     if dw_dtype is None:
         dw_dtype = io_dtype
     return AccLinearDesc(n, d_in, d_out, r, ldx, ldw, ldy, seed, row_offset, io_dtype, factor_dtype,
-                         dw_dtype, flags)
+                         dw_dtype, flags, ldf)
 
 
 def _ptr(t):
@@ -158,6 +160,11 @@ def acc_linear_bwd(desc, dY, W, Xs, dX, Gr, dW, workspace, stream=None, ws_bytes
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.acc_linear_bwd(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(Xs), _ptr(dX), _ptr(Gr),
                                _ptr(dW), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_dw(desc, Xs, Gr, dW, stream=None):
+    """Enqueue dW = Xs.Gr (+= with ACC_FLAG_DW_ACCUMULATE) from the two factors alone."""
+    _check(_lib.acc_linear_dw(ctypes.byref(desc), _ptr(Xs), _ptr(Gr), _ptr(dW), _stream(stream)))
 
 
 def acc_linear_bias_grad(desc, dY, dB, workspace, stream=None, ws_bytes=None):

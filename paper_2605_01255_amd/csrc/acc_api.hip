@@ -37,6 +37,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 struct Shape {
   int64_t n, d_in, d_out, r, ldx, ldw, ldy;
+  int64_t ldf;  // row stride of the factors whose rows hold r elements
 };
 
 int validate_desc(const acc_linear_desc* d, Shape* s, uint32_t extra_flags = 0) {
@@ -59,6 +60,8 @@ int validate_desc(const acc_linear_desc* d, Shape* s, uint32_t extra_flags = 0) 
   s->ldy = d->ldy ? d->ldy : d->d_out;
   if (s->ldx < s->d_in || s->ldw < w_row || s->ldy < s->d_out) return ACC_ERR_SHAPE;
   if (s->ldx % 8 || s->ldw % 8 || s->ldy % 8) return ACC_ERR_SHAPE;
+  s->ldf = d->ldf ? d->ldf : d->r;
+  if (s->ldf < s->r || s->ldf % 8 || s->ldf > ((int64_t)1 << 24)) return ACC_ERR_SHAPE;
   return ACC_OK;
 }
 
@@ -174,7 +177,7 @@ void generic_gemm_io(int32_t dt, const GemmParams& p, Launcher& L) {
 
 // partial[g][...] = A^T-slab . S-slab, fp32, then K4 reduce into `out` (factor dtype).
 void generic_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
-                    int64_t c_sm, int64_t c_sn, void* out, float* ws, Launcher& L) {
+                    int64_t c_sm, int64_t c_sn, void* out, int64_t out_row, int64_t out_ld, float* ws, Launcher& L) {
   GemmParams p{};
   p.A = A; p.B = nullptr; p.C = ws;
   p.M = channels; p.N = d->r; p.K = n;
@@ -189,9 +192,11 @@ void generic_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_
   const int64_t count = channels * d->r;
   const unsigned blocks = (unsigned)ceil_div(count, 1024);
   if (d->factor_dtype == ACC_BF16)
-    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (bf16*)out);
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (bf16*)out, out_row,
+      out_ld);
   else
-    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (float*)out);
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), (const float*)ws, G, count, count, (float*)out, out_row,
+      out_ld);
 }
 
 // Where a product of the two factors goes: the dense gradient, or the weight itself (optimizer step).
@@ -209,11 +214,11 @@ void generic_dw(const acc_linear_desc* d, const Shape& s, const void* Xs, const 
   if (d->flags & ACC_FLAG_W_OUT_IN) {  // [d_out, d_in] = Gr [d_out, r] . Xs^T
     p.A = Gr; p.B = Xs; p.C = o.C;
     p.M = s.d_out; p.N = s.d_in; p.K = s.r;
-    p.a_sm = s.r; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.r; p.c_sm = o.ld; p.c_sn = 1;
+    p.a_sm = s.ldf; p.a_sk = 1; p.b_sk = 1; p.b_sn = s.ldf; p.c_sm = o.ld; p.c_sn = 1;
   } else {
     p.A = Xs; p.B = Gr; p.C = o.C;
     p.M = s.d_in; p.N = s.d_out; p.K = s.r;
-    p.a_sm = s.r; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = o.ld; p.c_sn = 1;
+    p.a_sm = s.ldf; p.a_sk = 1; p.b_sk = s.d_out; p.b_sn = 1; p.c_sm = o.ld; p.c_sn = 1;
   }
   p.k_per_split = round_up(s.r, 32);
   p.accumulate = o.accumulate ? 1 : 0;
@@ -242,6 +247,7 @@ struct ReduceJob {
   int64_t count;
   int G;
   int out_bf16;
+  int64_t row, ld;  // the result's rows hold `row` elements and are stored `ld` apart
 };
 
 template <bool KMAJ, typename TC>
@@ -256,6 +262,7 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
   if (job && job->count) {
     p.red_part = job->part; p.red_out = job->out; p.red_count = job->count; p.red_G = job->G;
     p.red_out_bf16 = job->out_bf16;
+    p.red_row = job->row; p.red_ld = job->ld;
   }
   const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
   if (big_tiles >= 192) {  // 256 x 256 tiles: enough tiles to fill 256 CUs.  4 waves of 128 x 128 read a third
@@ -357,17 +364,19 @@ SketchPlan plan_sketch(const acc_linear_desc* d, int64_t n, int64_t channels, in
   return sp;
 }
 
-void reduce_partials(const acc_linear_desc* d, const float* ws, int G, int64_t count, void* out, Launcher& L) {
+void reduce_partials(const acc_linear_desc* d, const float* ws, int G, int64_t count, void* out, int64_t row,
+                     int64_t ld, Launcher& L) {
   const unsigned blocks = (unsigned)ceil_div(count, 1024);
   if (d->factor_dtype == ACC_BF16)
-    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), ws, G, count, count, (bf16*)out);
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), ws, G, count, count, (bf16*)out, row, ld);
   else
-    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), ws, G, count, count, (float*)out);
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), ws, G, count, count, (float*)out, row, ld);
 }
 
 // partial[g] (final orientation) with the tuned kernel, then K4 into `out`.
 void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, int64_t lda, int64_t channels,
-                 int64_t n, bool transposed, void* out, float* ws, Launcher& L, ReduceJob* defer) {
+                 int64_t n, bool transposed, void* out, int64_t out_row, int64_t out_ld, float* ws, Launcher& L,
+                 ReduceJob* defer) {
   SketchFastParams p{};
   p.A = (const bf16*)A; p.part = ws; p.n = n; p.C = channels; p.lda = lda; p.r = (int)d->r;
   p.tokens_per_split = sp.tokens_per_split; p.n_cslab = sp.n_cslab; p.n_js = sp.n_js; p.G = sp.G;
@@ -381,8 +390,8 @@ void fast_sketch(const acc_linear_desc* d, const SketchPlan& sp, const void* A, 
     if (transposed) L.launch_lds(sketch8_kernel<true, 2>, grid, dim3(512), (size_t)sketch8_lds_bytes<2>(), p);
     else L.launch_lds(sketch8_kernel<false, 2>, grid, dim3(512), (size_t)sketch8_lds_bytes<2>(), p);
   }
-  if (defer) *defer = ReduceJob{ws, out, channels * d->r, sp.G, d->factor_dtype == ACC_BF16 ? 1 : 0};
-  else reduce_partials(d, ws, sp.G, channels * d->r, out, L);
+  if (defer) *defer = ReduceJob{ws, out, channels * d->r, sp.G, d->factor_dtype == ACC_BF16 ? 1 : 0, out_row, out_ld};
+  else reduce_partials(d, ws, sp.G, channels * d->r, out, out_row, out_ld, L);
 }
 
 // One launch for the exact GEMM and the sketch of the same input (see acc_fused.h), then K4.
@@ -396,8 +405,8 @@ bool fused_ok(const acc_linear_desc* d, const SketchPlan& sp, int64_t n, int64_t
 
 template <bool KMAJ, bool TRANSPOSED>
 void fused_pass(const acc_linear_desc* d, const SketchPlan& sp, const void* A, const void* B, void* C, int64_t n,
-                int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, void* factor_out, float* ws,
-                Launcher& L) {
+                int64_t N, int64_t K, int64_t lda, int64_t ldb, int64_t ldc, void* factor_out, int64_t out_row,
+                int64_t out_ld, float* ws, Launcher& L) {
   FastGemmParams gp{};
   gp.A = (const bf16*)A; gp.B = (const bf16*)B; gp.C = C;
   gp.M = n; gp.N = N; gp.K = K; gp.lda = lda; gp.ldb = ldb; gp.ldc = ldc;
@@ -413,17 +422,19 @@ void fused_pass(const acc_linear_desc* d, const SketchPlan& sp, const void* A, c
   fm.period = n_gg / fm.n_units;
   const unsigned grid = (unsigned)(n_gg + fm.n_units * fm.unit) * 8u;
   L.launch_lds(fused_linear_kernel<KMAJ, TRANSPOSED>, dim3(grid), dim3(512), (size_t)128 * 1024, gp, sk, fm);
-  reduce_partials(d, ws, sp.G, K * d->r, factor_out, L);
+  reduce_partials(d, ws, sp.G, K * d->r, factor_out, out_row, out_ld, L);
 }
 
 // defer != nullptr: the caller launches a tuned GEMM next and wants it to fold the partials; the job is
 // filled in when the tuned sketch ran (its partials are pending), left empty otherwise.
+// The factor comes out [channels, r] with rows `ldf` apart, or transposed [r, channels] (dense).
 void run_sketch(const acc_linear_desc* d, const void* A, int64_t lda, int64_t channels, int64_t n,
-                bool transposed, void* out, float* ws, Launcher& L, ReduceJob* defer = nullptr) {
+                bool transposed, void* out, int64_t ldf, float* ws, Launcher& L, ReduceJob* defer = nullptr) {
   const SketchPlan sp = plan_sketch(d, n, channels, lda);
-  if (sp.fast) fast_sketch(d, sp, A, lda, channels, n, transposed, out, ws, L, defer);
-  else if (transposed) generic_sketch(d, A, lda, channels, n, 1, channels, out, ws, L);
-  else generic_sketch(d, A, lda, channels, n, d->r, 1, out, ws, L);
+  const int64_t row = transposed ? channels : d->r, ld = transposed ? channels : ldf;
+  if (sp.fast) fast_sketch(d, sp, A, lda, channels, n, transposed, out, row, ld, ws, L, defer);
+  else if (transposed) generic_sketch(d, A, lda, channels, n, 1, channels, out, row, ld, ws, L);
+  else generic_sketch(d, A, lda, channels, n, d->r, 1, out, row, ld, ws, L);
 }
 
 // ---- RSVD compressor ------------------------------------------------------------------------
@@ -501,8 +512,10 @@ void rsvd_gemm(int a_dt, int b_dt, int c_dt, const GemmParams& p, int splits, La
 
 void reduce_to(int out_dt, const float* part, int G, int64_t count, void* out, Launcher& L) {
   const unsigned blocks = (unsigned)ceil_div(count, 1024);
-  if (out_dt == ACC_BF16) L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), part, G, count, count, (bf16*)out);
-  else L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out);
+  if (out_dt == ACC_BF16)
+    L(reduce_partials_kernel<bf16>, dim3(blocks), dim3(256), part, G, count, count, (bf16*)out, count, count);
+  else
+    L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out, count, count);
 }
 
 // One Cholesky-QR pass on a tall matrix Yin [m, k] fp32: Q = Yin . R^-1 with Yin^T.Yin = R^T.R.  Q goes to any
@@ -622,16 +635,16 @@ void exact_backward_gemm(const acc_linear_desc* desc, const Shape& s, const void
 void factor_product(const acc_linear_desc* desc, const Shape& s, const void* Xs, const void* Gr,
                     const FactorProductOut& o, Launcher& L) {
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
-  if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.r, s.r)) {
+  if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.ldf, s.ldf)) {
     if (o.dtype == ACC_BF16)
-      fast_gemm<true, bf16>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.r, s.r, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+      fast_gemm<true, bf16>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
     else
-      fast_gemm<true, float>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.r, s.r, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
-  } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.r, s.d_out)) {
+      fast_gemm<true, float>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+  } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.ldf, s.d_out)) {
     if (o.dtype == ACC_BF16)
-      fast_gemm<false, bf16>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.r, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+      fast_gemm<false, bf16>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
     else
-      fast_gemm<false, float>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.r, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
+      fast_gemm<false, float>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
   } else {
     generic_dw(desc, s, Xs, Gr, o, L);
   }
@@ -649,6 +662,7 @@ int validate_rsvd(const acc_linear_desc* d, Shape* s) {
   const int rc = validate_desc(d, s, 3u << ACC_FLAG_RSVD_POWER_SHIFT);
   if (rc != ACC_OK) return rc;
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
+  if (s->ldf != s->r) return ACC_ERR_SHAPE;  // the RSVD factors are dense
   if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
   return ACC_OK;
 }
@@ -660,6 +674,7 @@ int validate_lowrank(const acc_linear_desc* d, Shape* s, int64_t k, bool for_pro
   const int rc = validate_desc(d, s);
   if (rc != ACC_OK) return rc;
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
+  if (s->ldf != s->r) return ACC_ERR_SHAPE;  // the optimizer calls read dense factors
   if (k < 0 || k % 8 || k > s->d_in || k > (1 << 16)) return ACC_ERR_SHAPE;
   if (for_projector && (k < 8 || k > kRsvdMaxRank || k > s->r)) return ACC_ERR_SHAPE;
   return ACC_OK;
@@ -748,14 +763,15 @@ int enqueue_forward(const acc_linear_desc* desc, const Shape& s, const void* X, 
   Launcher L{stream};
   const SketchPlan sp_f = plan_sketch(desc, s.n, s.d_in, s.ldx);
   if (sketch && fused_ok(desc, sp_f, s.n, s.d_out, s.d_in, s.ldx, s.ldw)) {
-    fused_pass<false, false>(desc, sp_f, X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, Xs, workspace, L);
+    fused_pass<false, false>(desc, sp_f, X, W, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, Xs, s.r, s.ldf, workspace, L);
     return L.status();
   }
   // Sketch first: it pulls X through the memory-side cache, so the GEMM that follows starts from
   // there rather than from HBM (measured 4 % on the whole pass against the opposite order).
   ReduceJob job{};  // with a tuned GEMM next, the sketch leaves its K4 reduction to that launch
   if (sketch)
-    run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, workspace, L, forward_gemm_is_tuned(desc, s) ? &job : nullptr);
+    run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, s.ldf, workspace, L,
+               forward_gemm_is_tuned(desc, s) ? &job : nullptr);
   exact_forward_gemm(desc, s, X, W, Y, L, &job);
   return L.status();
 }
@@ -824,10 +840,11 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
   if (fused_b) {
     // W is [N = d_in, K = d_out]; the sketched matrix dY is the GEMM's left operand
-    fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, (float*)workspace, L);
+    fused_pass<true, true>(desc, sp_b, dY, W, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, Gr, s.d_out, s.d_out,
+                           (float*)workspace, L);
   } else {
     ReduceJob job{};
-    run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, (float*)workspace, L,
+    run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, s.ldf, (float*)workspace, L,
                backward_gemm_is_tuned(desc, s) ? &job : nullptr);
     exact_backward_gemm(desc, s, dY, W, dX, L, &job);
   }
@@ -961,6 +978,19 @@ int acc_linear_bwd_rsvd(const acc_linear_desc* desc, const void* dY, const void*
   else rsvd_factor(desc, s, pl, (char*)workspace, dY, s.ldy, s.d_out, U, !w_oi, Gr, L);
   exact_backward_gemm(desc, s, dY, W, dX, L);
   if (dW) dense_dw(desc, s, V, Gr, dW, L);
+  return L.status();
+}
+
+int acc_linear_dw(const acc_linear_desc* desc, const void* Xs, const void* Gr, void* dW, void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (desc->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
+  if (!Xs || !Gr || !dW) return ACC_ERR_INVALID_ARG;
+  if (!aligned16(Xs) || !aligned16(Gr) || !aligned16(dW)) return ACC_ERR_ALIGN;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  dense_dw(desc, s, Xs, Gr, dW, L);
   return L.status();
 }
 
@@ -1131,6 +1161,7 @@ int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* h
   }
   Shape sb = s;
   sb.r = kk;
+  sb.ldf = kk;
   const FactorProductOut o{W, desc->io_dtype, s.ldw, true, -hyper->lr * hyper->scale,
                            1.f - hyper->lr * hyper->weight_decay};
   factor_product(desc, sb, P ? P : left, nrm, o, L);

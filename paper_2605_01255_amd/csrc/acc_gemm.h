@@ -37,6 +37,7 @@ struct FastGemmParams {
   int64_t red_stride;     // elements all work-groups of the launch cover per sweep: grid * threads * 4
   int red_G;
   int red_out_bf16;       // 1: red_out is bf16, 0: float
+  int64_t red_row, red_ld;  // the result has rows of red_row elements (red_row % 4 == 0) stored red_ld apart
   int accumulate;         // 0: C = A . B;  1: C = beta C + alpha (A . B) (a bf16 C rounds the product, then the sum)
   float alpha, beta;      // used when accumulate; 1, 1 is the plain sum
   // Optional split of the K range over work-groups (skinny products whose M x N tiles alone do not fill
@@ -318,13 +319,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
       f32x4 sum = *(const f32x4*)(p.red_part + e);
 #pragma unroll 8
       for (int g = 1; g < p.red_G; ++g) sum += *(const f32x4*)(p.red_part + (int64_t)g * p.red_count + e);
+      const int64_t eo = p.red_ld == p.red_row ? e : (e / p.red_row) * p.red_ld + e % p.red_row;
       if (p.red_out_bf16) {
         bf16x4 v;
 #pragma unroll
         for (int t = 0; t < 4; ++t) v[t] = (bf16)sum[t];
-        *(bf16x4*)((bf16*)p.red_out + e) = v;
+        *(bf16x4*)((bf16*)p.red_out + eo) = v;
       } else {
-        *(f32x4*)((float*)p.red_out + e) = sum;
+        *(f32x4*)((float*)p.red_out + eo) = sum;
       }
     }
     if (!has_tile) return;

@@ -299,13 +299,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_persist_kernel(FastGemmParams p
       f32x4 sum = *(const f32x4*)(p.red_part + e);
 #pragma unroll 8
       for (int g = 1; g < p.red_G; ++g) sum += *(const f32x4*)(p.red_part + (int64_t)g * p.red_count + e);
+      const int64_t eo = p.red_ld == p.red_row ? e : (e / p.red_row) * p.red_ld + e % p.red_row;
       if (p.red_out_bf16) {
         bf16x4 v;
 #pragma unroll
         for (int t = 0; t < 4; ++t) v[t] = (bf16)sum[t];
-        *(bf16x4*)((bf16*)p.red_out + e) = v;
+        *(bf16x4*)((bf16*)p.red_out + eo) = v;
       } else {
-        *(f32x4*)((float*)p.red_out + e) = sum;
+        *(f32x4*)((float*)p.red_out + eo) = sum;
       }
     }
   }

@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
 template <typename TO>
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int G,
                                                               int64_t stride, int64_t count,
-                                                              TO* __restrict__ out) {
+                                                              TO* __restrict__ out, int64_t row, int64_t ld) {
   const int64_t e = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (e >= count) return;
   f32x4 s = *(const f32x4*)(part + e);
@@ -149,8 +149,9 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __res
     const f32x4 v = *(const f32x4*)(part + (int64_t)g * stride + e);
     s += v;
   }
+  const int64_t eo = ld == row ? e : (e / row) * ld + e % row;  // rows of `row` elements stored `ld` apart
 #pragma unroll
-  for (int t = 0; t < 4; ++t) out[e + t] = from_f32<TO>(s[t]);
+  for (int t = 0; t < 4; ++t) out[eo + t] = from_f32<TO>(s[t]);
 }
 
 // Column sums over a slab of rows (bias gradient, proof of Thm 3.2.2, bias term):

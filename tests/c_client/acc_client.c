@@ -27,7 +27,7 @@ int main(void) {
   d.ldx = 0; d.ldw = 0; d.ldy = 0;
   d.seed = 1234; d.row_offset = 0;
   d.io_dtype = ACC_F32; d.factor_dtype = ACC_F32; d.dw_dtype = ACC_F32;
-  d.flags = 0;
+  d.flags = 0; d.ldf = 0;
   if (acc_version() < 100) { fprintf(stderr, "bad version\n"); return 1; }
 
   float *hX = malloc(sizeof(float) * n * d_in), *hW = malloc(sizeof(float) * d_in * d_out);

@@ -35,7 +35,7 @@ def test_descriptor_layout_matches_header():
     ctype = {"int64_t": ctypes.c_int64, "uint64_t": ctypes.c_uint64, "int32_t": ctypes.c_int32,
              "uint32_t": ctypes.c_uint32}
     assert [(n, ctype[t]) for t, n in fields] == list(acc.AccLinearDesc._fields_)
-    assert ctypes.sizeof(acc.AccLinearDesc) == 88
+    assert ctypes.sizeof(acc.AccLinearDesc) == 96
 
 
 def test_version_and_status_strings():
@@ -238,3 +238,22 @@ def test_static_scratch_forward_validates_before_it_touches_a_device():
     header = open(HEADER).read()
     assert re.search(r"#define ACC_STATIC_SCRATCH_BYTES \(\(size_t\)32 << 20\)", header)
     assert acc.ACC_STATIC_SCRATCH_BYTES == 32 << 20
+
+
+def test_factor_stride_and_the_dense_gradient_call_are_validated():
+    ok = dict(n=256, d_in=256, d_out=512, r=16)
+    for bad in (8, 20, 12, (1 << 24) + 8):          # smaller than r, not a multiple of 8, above the limit
+        assert _fwd(acc.make_desc(**ok, ldf=bad)) == -2, bad
+    assert _fwd(acc.make_desc(**ok, ldf=48)) in (0, -6)
+    f = acc._lib.acc_linear_dw
+    d = acc.make_desc(**ok, ldf=48)
+    assert f(None, 0x1000, 0x2000, 0x3000, None) == -1
+    assert f(ctypes.byref(d), 0, 0x2000, 0x3000, None) == -1
+    assert f(ctypes.byref(d), 0x1000, 0x2000, 0, None) == -1
+    assert f(ctypes.byref(d), 0x1000, 0x2008, 0x3000, None) == -3
+    assert f(ctypes.byref(acc.make_desc(**ok, flags=acc.ACC_FLAG_SKIP_SKETCH)), 0x1000, 0x2000, 0x3000, None) == -1
+    assert f(ctypes.byref(acc.make_desc(**ok, flags=acc.ACC_FLAG_DW_ACCUMULATE)), 0x1000, 0x2000, 0x3000, None) in (0, -6)
+    # the RSVD and optimizer calls read dense factors only
+    r = acc.make_desc(n=256, d_in=256, d_out=512, r=32, ldf=64)
+    assert acc.acc_rsvd_workspace_bytes(r, False) == 0
+    assert acc.acc_lowrank_workspace_bytes(r, 16) == 0
