@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--buffer-sets", type=int, default=3, help="rotated so no tensor stays in the 256 MB cache")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="instead of the layer: time the register-only bf16 MFMA loop (acc_probe_mfma) on zero and on "
+                         "random operands, both instruction shapes, one and two waves per SIMD (own JSON line)")
     ap.add_argument("--traffic-mb", type=float, default=None,
                     help="HBM-side MB per launch of the dominant kernel, from rocprofv3 --pmc runs; default: the figure "
                          "stored beside the counter summary of this workload under profiles/, null if there is none")
@@ -154,6 +157,27 @@ def run_layer(args, torch, acc, inputs, dev):
                              "dense_per_token": dense / n, "kept_per_token": round(kept / n, 3)}}), flush=True)
 
 
+def run_mfma_ceiling(args, torch, acc, dev):
+    """What the matrix pipe sustains with nothing else running: the practical ceiling of the MFMA-bound steps."""
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=dev)
+    iters, rows = 20000, []
+    for shape, name in ((0, "32x32x16"), (1, "16x16x32")):
+        for waves in (1, 2):
+            for rnd in (0, 1):
+                def launch(_):
+                    return acc.acc_probe_mfma(shape, waves, rnd, iters, sink)
+                flops = launch(0)
+                for i in range(max(2, args.warmup // 20)):     # ~1 ms per launch: the clocks settle under load
+                    launch(i)
+                ms = time_events(torch, launch, max(5, args.steps // 10))
+                rows.append({"mfma": name, "waves_per_simd": waves, "operands": "random bf16" if rnd else "zeros",
+                             "ms_per_launch": round(ms, 4), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                             "frac_of_2500": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)})
+    print(json.dumps({"metric": "register-only bf16 MFMA loop TFLOP/s", "unit": "TFLOP/s", "n_gpus": 1,
+                      "config": {"workload": f"256 work-groups, {iters} x 4 matrix instructions per wave"},
+                      "rows": rows}), flush=True)
+
+
 def cpu_baseline(lin, data, with_dw, budget_tokens):
     """The oracle, as it stands, timed on a bounded token sample of the same workload."""
     import numpy as np
@@ -193,6 +217,9 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.mfma_ceiling:
+        run_mfma_ceiling(args, torch, acc, dev)
+        return
     if args.layer:
         run_layer(args, torch, acc, inputs, dev)
         return

@@ -25,7 +25,7 @@ EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_fwd_stati
            "acc_linear_bias_grad",
            "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_lowrank_workspace_bytes",
            "acc_lowrank_projector", "acc_lowrank_adamw_step",
-           "acc_philox_dump_u32",
+           "acc_philox_dump_u32", "acc_probe_mfma",
            "acc_sketch_dump", "acc_status_string", "acc_version")
 
 
@@ -90,6 +90,9 @@ _lib.acc_philox_dump_u32.restype = ctypes.c_int
 _lib.acc_philox_dump_u32.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64, _vp, _vp]
 _lib.acc_sketch_dump.restype = ctypes.c_int
 _lib.acc_sketch_dump.argtypes = [_dp, _vp, _vp]
+_lib.acc_probe_mfma.restype = ctypes.c_int
+_lib.acc_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, _vp, _sz,
+                                ctypes.POINTER(ctypes.c_double), _vp]
 _lib.acc_status_string.restype = ctypes.c_char_p
 _lib.acc_status_string.argtypes = [ctypes.c_int]
 _lib.acc_version.restype = ctypes.c_int
@@ -98,6 +101,14 @@ _lib.acc_version.argtypes = []
 
 def status_string(status: int) -> str:
     return _lib.acc_status_string(int(status)).decode()
+
+
+def acc_probe_mfma(shape, waves_per_simd, random_data, iters, sink, stream=None) -> float:
+    """Enqueue one launch of the register-only MFMA loop; returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(_lib.acc_probe_mfma(shape, waves_per_simd, 1 if random_data else 0, iters, _ptr(sink),
+                               sink.numel() * sink.element_size(), ctypes.byref(flops), _stream(stream)))
+    return flops.value
 
 
 def acc_version() -> int:

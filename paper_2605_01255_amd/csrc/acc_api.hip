@@ -15,6 +15,7 @@
 #include "acc_gemm.h"
 #include "acc_generic.h"
 #include "acc_optim.h"
+#include "acc_probe.h"
 #include "acc_rsvd.h"
 #include "acc_sketch.h"
 #include "acc_gemm_persist.h"
@@ -1195,6 +1196,23 @@ int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream) {
   Launcher L{(hipStream_t)stream};
   if (desc->io_dtype == ACC_F32) L(sketch_dump_kernel<true>, grid, dim3(256), sk, desc->n, desc->r, S);
   else L(sketch_dump_kernel<false>, grid, dim3(256), sk, desc->n, desc->r, S);
+  return L.status();
+}
+
+int acc_probe_mfma(int shape, int waves_per_simd, int random_data, int64_t iters, float* sink, size_t sink_bytes,
+                   double* flops, void* stream) {
+  if (!sink || !flops) return ACC_ERR_INVALID_ARG;
+  if ((shape != 0 && shape != 1) || (waves_per_simd != 1 && waves_per_simd != 2) || iters < 1 || iters > (1 << 24))
+    return ACC_ERR_SHAPE;
+  if (!aligned16(sink)) return ACC_ERR_ALIGN;
+  const unsigned threads = 256u * (unsigned)waves_per_simd, groups = 256;  // one work-group per compute unit
+  if (sink_bytes < (size_t)groups * threads * sizeof(float)) return ACC_ERR_WORKSPACE;
+  int rc = check_device();
+  if (rc != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  if (shape == 0) L(mfma_probe_kernel<0>, dim3(groups), dim3(threads), random_data, iters, sink);
+  else L(mfma_probe_kernel<1>, dim3(groups), dim3(threads), random_data, iters, sink);
+  *flops = (double)groups * (threads / 64) * (double)iters * 4.0 * (shape == 0 ? 32768.0 : 16384.0);
   return L.status();
 }
 

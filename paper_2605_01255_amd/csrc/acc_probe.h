@@ -1,0 +1,69 @@
+// Measurement hook: the rate of the bf16 matrix instructions in a loop that touches nothing but registers.
+// It frames every MFMA-bound figure of the library: the published peak assumes 2.4 GHz, and what the part
+// sustains depends on the operand values (switching activity) through its power limit.
+//
+// Every wave keeps four independent accumulator sets and four operand pairs in registers and issues
+// iters x 4 matrix instructions; operands are all zero, or pseudo-random bf16 values with magnitudes 1/8 .. 16.
+// The sums go to `sink` so that the loop cannot be dropped.
+#pragma once
+#include "acc_common.h"
+
+namespace acc {
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+// bf16 with random sign and mantissa and an exponent of 124 .. 131
+__device__ __forceinline__ bf16 probe_value(uint32_t h) {
+  const uint16_t bits = (uint16_t)((h & 0x807Fu) | ((124u + ((h >> 8) & 7u)) << 7));
+  return __builtin_bit_cast(bf16, bits);
+}
+
+// SHAPE 0: v_mfma_f32_32x32x16_bf16 (32768 flops), SHAPE 1: v_mfma_f32_16x16x32_bf16 (16384 flops)
+template <int SHAPE>
+__global__ __launch_bounds__(512) void mfma_probe_kernel(int random_data, int64_t iters, float* __restrict__ sink) {
+  const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      a[j][e] = random_data ? probe_value(probe_hash(gid * 64u + j * 16u + e)) : (bf16)0.f;
+      b[j][e] = random_data ? probe_value(probe_hash(gid * 64u + j * 16u + 8u + e)) : (bf16)0.f;
+    }
+  float total = 0.f;
+  if constexpr (SHAPE == 0) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[j], acc[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) total += acc[j][e];
+  } else {
+    f32x4 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[j][e] = 0.f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[j], b[j], acc[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) total += acc[j][e];
+  }
+  sink[gid] = total;
+}
+
+}  // namespace acc

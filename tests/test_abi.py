@@ -257,3 +257,16 @@ def test_factor_stride_and_the_dense_gradient_call_are_validated():
     r = acc.make_desc(n=256, d_in=256, d_out=512, r=32, ldf=64)
     assert acc.acc_rsvd_workspace_bytes(r, False) == 0
     assert acc.acc_lowrank_workspace_bytes(r, 16) == 0
+
+
+def test_mfma_probe_hook_validates_arguments():
+    f = acc._lib.acc_probe_mfma
+    fl = ctypes.c_double(0.0)
+    big = 256 * 512 * 4
+    assert f(0, 1, 0, 100, None, big, ctypes.byref(fl), None) == -1
+    assert f(0, 1, 0, 100, 0x1000, big, None, None) == -1
+    assert f(2, 1, 0, 100, 0x1000, big, ctypes.byref(fl), None) == -2
+    assert f(0, 3, 0, 100, 0x1000, big, ctypes.byref(fl), None) == -2
+    assert f(0, 1, 0, 0, 0x1000, big, ctypes.byref(fl), None) == -2
+    assert f(0, 1, 0, 100, 0x1004, big, ctypes.byref(fl), None) == -3
+    assert f(1, 2, 1, 100, 0x1000, 256 * 512 * 4 - 1, ctypes.byref(fl), None) == -5
