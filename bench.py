@@ -256,15 +256,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # Order of the legs: single steps and the rows beside the headline run first, then the headline region
-    # (warm-up, timed steps), then the per-phase and single-kernel timings.  The part raises its clocks over the
-    # first 20-30 ms of load after idling (measured: single steps 0.77, 0.75, 0.72, ... 0.60 ms when the region
-    # starts 3 ms after idle, 0.58 ms once settled), and host-side input generation leaves it idle for seconds,
-    # so a region that came first with a short warm-up would time that ramp; `timed_region` shows the single
-    # steps of the region either way.
+    # Order of the legs: the rows beside the headline run first (small kernels, then the layer in the other weight
+    # orientation and single steps), then the headline region (warm-up, timed steps), then the per-phase and
+    # single-kernel timings.  The part raises its clocks over the first 20-30 ms of heavy load after idling or after
+    # a run of small kernels (measured: single steps 0.77, 0.75, 0.72, ... 0.60 ms when the region starts 3 ms after
+    # idle, 0.58 ms once settled), and host-side input generation leaves it idle for seconds, so a region that came
+    # first with a short warm-up would time that ramp; `timed_region` shows the single steps of the region either way.
     flops = lin.flops(with_dw)
     step(0)
-    step_median, step_min = time_each(torch, step, args.steps)
     # rows added after the hot path: bias gradient (HBM-bound column sum of dY) and the layer with W in
     # the [d_out, d_in] orientation; reported beside the headline, not part of `value`
     tdt = acc.torch_dtype(code)
@@ -288,7 +287,6 @@ def main():
         acc.acc_linear_bwd(desc_oi, b.dY, w_oi[i % len(sets)], b.Xs, b.dX, gr_oi, dw_oi, ws_b)
 
     step_oi(0)
-    ms_oi = time_events(torch, step_oi, args.steps)
     # RSVD compressor at the paper's rank 32 on the same layer (U [n, 32] + V [d_in, 32] kept)
     k_rsvd = 32
     desc_rs = acc.make_desc(lin.n, lin.d_in, lin.d_out, k_rsvd, seed=lin.seed, io_dtype=code)
@@ -349,6 +347,9 @@ def main():
     ms_optk = time_events(torch, opt_step_projected, args.steps)
     ms_optr = time_events(torch, opt_step_left, args.steps)
     w_bytes = 2 * lin.d_in * lin.d_out * (2 if lin.dtype == "bf16" else 4)   # W read and written once
+    # the heavy legs last: the small kernels above let the clocks fall again
+    ms_oi = time_events(torch, step_oi, args.steps)
+    step_median, step_min = time_each(torch, step, args.steps)
     widened = {
         "lowrank_adamw": {"projector_rank": k_opt, "ms_step_projected": round(ms_optk, 4),
                           "ms_step_left_factor_as_projector": round(ms_optr, 4),

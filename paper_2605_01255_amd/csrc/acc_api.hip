@@ -18,7 +18,7 @@
 #include "acc_probe.h"
 #include "acc_rsvd.h"
 #include "acc_sketch.h"
-#include "acc_gemm_persist.h"
+#include "acc_gemm16.h"
 
 // Scratch of acc_linear_fwd_static (the entry point for callers that cannot allocate): the split-token partial
 // tiles of the sketch live here instead of in a caller's workspace.  Every GPU the library runs on holds its own
@@ -274,7 +274,7 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
       if (!accumulate && grid > 256 && K >= 192) {
         // several rounds of tiles: 256 persistent work-groups
         p.red_stride = (int64_t)256 * 256 * 4;
-        L.launch_lds(gemm_bf16_persist_kernel<KMAJ>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)grid);
+        L.launch_lds(gemm16_persist_kernel<KMAJ>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)grid);
         return;
       }
       if (!accumulate) {  // the epilogue folded into the last K tile
