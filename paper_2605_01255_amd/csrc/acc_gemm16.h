@@ -28,7 +28,9 @@
 // ms against 0.553 - 0.557 before slot 80; before slot 88 0.545 - 0.546 against 0.541 - 0.542 before slot 80; all
 // sixteen wave-loads after the barrier, one every three slots, 0.565 against 0.553 - 0.557; eight after it and
 // eight in the next k-step 0: equal; one wave-load every second slot: thirty times slower (the transfers queue up
-// behind each other), never do that.
+// behind each other), never do that.  Spreading the wave-loads evenly (nine after the barrier, one every six
+// slots, seven in the next k-step 0, one every six) 0.5545 against 0.5507; the last of them 14 slots before the
+// barrier instead of 58: 0.584 (the transfers need their thousand clocks to land).
 // Two waves per SIMD (eight waves of 128 x 64) run equal to four waves: what the second wave hides in issue
 // gaps it pays back in LDS operand reads (1.5 x).
 #pragma once
@@ -58,12 +60,12 @@ __device__ __forceinline__ int swz_n16(int krow) { return ((krow & 3) << 2) | ((
 //     accumulators (slots 48 and 56).
 // LDS: two 64 KB stages + 32 KB of staging regions = 160 KB.  Restrictions (host): bf16 output, no accumulation
 // into C, no K split, K >= 192.
-template <bool B_KMAJOR>
+template <bool B_KMAJOR, int N1 = 12, int S1 = 4, int S0 = 4>
 __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, int n_slots) {
   // schedule of k-step 1: the barrier sits before its slot BAR_Q; N1 wave-loads go out after it, one every S1
-  // slots, the other 16 - N1 in the next K tile's k-step 0, one every four slots from slot 2
-  constexpr int BAR_Q = 8, N1 = 12, S1 = 4;
-  static_assert(BAR_Q + 2 + S1 * (N1 - 1) < 64, "wave-load slots");
+  // slots, the other 16 - N1 in the next K tile's k-step 0, one every S0 slots from slot 2
+  constexpr int BAR_Q = 8;
+  static_assert(BAR_Q + 2 + S1 * (N1 - 1) < 64 && 2 + S0 * (15 - N1) < 64, "wave-load slots");
   constexpr int AEARLY = BAR_Q / 8;  // A operands whose block row is done before the barrier
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int NW = 4, WN = 2, TB = 8;
@@ -235,7 +237,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       }
       if (j == 0 && i >= 1) a[i - 1] = read_a(cur, 1, i - 1);
       if (j == 4) b1[i] = read_b(cur, 1, i);
-      if (q < 4 * (NG - N1) && (q & 3) == 2) issue_one(ref1, N1 + (q >> 2), k1, nxt_lds);
+      if (q >= 2 && (q - 2) % S0 == 0 && (q - 2) / S0 < NG - N1) issue_one(ref1, N1 + (q - 2) / S0, k1, nxt_lds);
       if (CARRY && q < 16) carry_slot(q);
       __builtin_amdgcn_sched_barrier(0);
     }
