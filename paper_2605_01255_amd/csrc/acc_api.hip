@@ -19,6 +19,7 @@
 #include "acc_rsvd.h"
 #include "acc_sketch.h"
 #include "acc_gemm16.h"
+#include "acc_gemm_smallk.h"
 
 // Scratch of acc_linear_fwd_static (the entry point for callers that cannot allocate): the split-token partial
 // tiles of the sketch live here instead of in a caller's workspace.  Every GPU the library runs on holds its own
@@ -291,6 +292,21 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
     L.launch_lds(gemm_bf16_kernel<2, 2, 2, 2, KMAJ, TC>, dim3(grid), dim3(256),
                  (size_t)gemm_bf16_lds_bytes<2, 2, 2, 2>(), p);
   }
+}
+
+// C (op)= A[M, K] . B for a short K on the three-stage kernel of acc_gemm_smallk.h (the product of two gradient
+// factors: the dense dW, the optimizer's update of W).
+template <bool KMAJ, typename TC>
+void smallk_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb,
+                 int64_t ldc, Launcher& L, bool accumulate, float alpha, float beta) {
+  FastGemmParams p{};
+  p.accumulate = accumulate ? 1 : 0;
+  p.alpha = alpha; p.beta = beta;
+  p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  p.tiles_m = (int)ceil_div(M, 192);
+  p.tiles_n = (int)ceil_div(N, 192);
+  L.launch_lds(gemm16_smallk_kernel<KMAJ, TC>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(256), (size_t)144 * 1024, p);
 }
 
 // K splits of a skinny product: as many as fill the chip's resident work-group slots exactly once (a
@@ -636,13 +652,27 @@ void exact_backward_gemm(const acc_linear_desc* desc, const Shape& s, const void
 void factor_product(const acc_linear_desc* desc, const Shape& s, const void* Xs, const void* Gr,
                     const FactorProductOut& o, Launcher& L) {
   const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;
+  // A few K tiles and at most one round of 192 x 192 tiles: the three-stage kernel (one exposed latency per
+  // work-group).  More tiles than compute units: the pipelined kernel, two work-groups per compute unit covering
+  // each other's waits (measured at 3072 x 8192, r = 256: 23.5 against 27.6 us).  One round, 3072 x 3072: 12.4 against
+  // 14.2 us at r = 256, 8.4 against 9.8 at r = 64; read-modify-write of a bf16 W at r = 64: 11.4 against 14.5 us
+  // (a plain in-place pass over the same 18.9 MB takes 7.4 us, a fill 4.7).
+  const bool short_k = s.r <= 1024 && ceil_div(s.d_in, 192) * ceil_div(s.d_out, 192) <= 256;
   if (w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_out, s.d_in, s.r, s.ldf, s.ldf)) {
-    if (o.dtype == ACC_BF16)
+    if (short_k && o.dtype == ACC_BF16)
+      smallk_gemm<true, bf16>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, o.accumulate, o.alpha, o.beta);
+    else if (short_k)
+      smallk_gemm<true, float>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, o.accumulate, o.alpha, o.beta);
+    else if (o.dtype == ACC_BF16)
       fast_gemm<true, bf16>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
     else
       fast_gemm<true, float>(Gr, Xs, o.C, s.d_out, s.d_in, s.r, s.ldf, s.ldf, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
   } else if (!w_oi && desc->factor_dtype == ACC_BF16 && fast_gemm_ok(s.d_in, s.d_out, s.r, s.ldf, s.d_out)) {
-    if (o.dtype == ACC_BF16)
+    if (short_k && o.dtype == ACC_BF16)
+      smallk_gemm<false, bf16>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, o.accumulate, o.alpha, o.beta);
+    else if (short_k)
+      smallk_gemm<false, float>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, o.accumulate, o.alpha, o.beta);
+    else if (o.dtype == ACC_BF16)
       fast_gemm<false, bf16>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
     else
       fast_gemm<false, float>(Xs, Gr, o.C, s.d_in, s.d_out, s.r, s.ldf, s.d_out, o.ld, L, nullptr, o.accumulate, o.alpha, o.beta);
