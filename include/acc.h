@@ -193,7 +193,8 @@ size_t acc_lowrank_workspace_bytes(const acc_linear_desc* desc, int64_t k);
 
 /* P [d_in, k] (dense, factor_dtype) is overwritten with the projector of the factored gradient left . Gr.
  * left [d_in, r] and Gr ([r, d_out], or [d_out, r] under ACC_FLAG_W_OUT_IN), both factor_dtype, are read.
- * k: multiple of 8, 8 <= k <= 64, k <= r, k <= d_in (else ACC_ERR_SHAPE).  If Yp has dependent columns
+ * k: multiple of 8, 8 <= k <= 512, k <= r, k <= d_in (else ACC_ERR_SHAPE; above 64 the k x k factorisation runs
+ * blocked on 64 x 64 diagonal blocks).  If Yp has dependent columns
  * (rank(G^_W) < k) the corresponding columns of P are zero. */
 int acc_lowrank_projector(const acc_linear_desc* desc, int64_t k, const void* left, const void* Gr, void* P,
                           void* workspace, size_t ws_bytes, void* stream);
@@ -215,7 +216,8 @@ int acc_lowrank_adamw_step(const acc_linear_desc* desc, const acc_adamw_hyper* h
  * final rotation to singular vectors, subspace iterations only on request (ACC_FLAG_RSVD_POWER_*):
  *   Omega [d_in, r] Gaussian, Omega[c, j] = the Philox normal of (seed, token index := c, column j);
  *   Yr = X.Omega;  Yr = U.R, U^T.U = I, diag(R) > 0 (Cholesky QR, applied twice);  V = X^T.U.
- * Here desc->r is the rank: multiple of 8, 8 <= r <= 64, r <= n, r <= d_in, ldf 0 or r (else ACC_ERR_SHAPE);
+ * Here desc->r is the rank: multiple of 8, 8 <= r <= 512, r <= n, r <= d_in, ldf 0 or r (else ACC_ERR_SHAPE; the
+ * paper uses 8 and 32; above 64 the r x r factorisation runs blocked on 64 x 64 diagonal blocks);
  * row_offset is ignored; ACC_FLAG_SKIP_SKETCH and ACC_FLAG_ONE_LAUNCH are refused.  If Yr has
  * dependent columns (rank(X) < r) the corresponding columns of U and V are zero; U.V^T is still the
  * projection of X onto the range of Yr.  U and V are stored as factor_dtype.                        */

@@ -465,7 +465,29 @@ struct RsvdPlan {
   int64_t n_pad;  // tokens rounded up to 64 (K padding of the products over tokens)
   size_t off_y0, off_q1, off_gram_part, off_gram, off_rinv, off_fact_part;  // byte offsets
   size_t off_omega, off_ut, off_yr_part, off_z0, off_z1, off_zt_part, total;
+  size_t off_rt;  // ranks above 64: the transposed triangular factor [k, k] of the blocked Cholesky
 };
+
+// Scratch of one Cholesky-QR pass at rank k.  Up to 64 the k x k factorisation is one launch on one wave; above it
+// runs blocked on 64 x 64 diagonal blocks and needs the full Gram matrix, the transposed factor and one triangular
+// image per block.
+constexpr int kGramSplitsBlocked = 16;
+struct QrScratch { size_t gram_part, gram, rinv, rt; };
+template <typename Take>
+QrScratch take_qr_scratch(int64_t k, int g_gram, Take& take) {
+  QrScratch q{};
+  if (k <= kRsvdMaxRank) {
+    q.gram_part = take((size_t)g_gram * k * k * 4);
+    q.gram = take((size_t)k * k * 4);
+    q.rinv = take(kCholImageBytes);
+  } else {
+    q.gram_part = take((size_t)kGramSplitsBlocked * k * k * 4);
+    q.gram = take((size_t)k * k * 4);
+    q.rinv = take(kCholImageBytes * (size_t)ceil_div(k, kRsvdMaxRank) + 256);  // + the matrix's largest diagonal entry
+    q.rt = take((size_t)k * k * 4);
+  }
+  return q;
+}
 
 // Rounds of subspace iteration asked for in the descriptor (RSVD entry points only).
 int rsvd_power_iters(const acc_linear_desc* d) { return (int)((d->flags >> ACC_FLAG_RSVD_POWER_SHIFT) & 3u); }
@@ -487,9 +509,8 @@ RsvdPlan plan_rsvd(const acc_linear_desc* d, const Shape& s, bool backward) {
   if (!backward) {
     pl.off_y0 = take((size_t)s.n * k * 4);
     pl.off_q1 = take((size_t)s.n * k * 4);
-    pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
-    pl.off_gram = take((size_t)k * k * 4);
-    pl.off_rinv = take(kCholImageBytes);
+    const QrScratch q = take_qr_scratch(k, pl.g_gram, take);
+    pl.off_gram_part = q.gram_part; pl.off_gram = q.gram; pl.off_rinv = q.rinv; pl.off_rt = q.rt;
     if (rsvd_power_iters(d)) {  // Z = X^T.U and its orthonormalised form, [d_in, k] fp32
       pl.off_z0 = take((size_t)s.d_in * k * 4);
       pl.off_z1 = take((size_t)s.d_in * k * 4);
@@ -535,38 +556,113 @@ void reduce_to(int out_dt, const float* part, int G, int64_t count, void* out, L
     L(reduce_partials_kernel<float>, dim3(blocks), dim3(256), part, G, count, count, (float*)out, count, count);
 }
 
+// The same pass for ranks above 64 (up to 512), built from the rank-64 kernels: blocked right-looking Cholesky of
+// the Gram matrix (diagonal block -> chol_factor_kernel<64>; the block column below it -> tall_solve_kernel<64>,
+// which gives the transposed row panel of R; trailing update on the generic GEMM), then Q = Yin . R^-1 block column
+// by block column (Y_j -= Q_{<j} . R_{<j, j} on the generic GEMM, Q_j = Y_j . R_jj^-1 by tall_solve_kernel<64>).
+// Yin is used as scratch: its columns are overwritten.  Q goes to Qf (fp32; Yin itself when Qf is null), Qt, Ut as
+// in cholesky_qr_pass.
+void cholesky_qr_pass_blocked(const Shape& s, const RsvdPlan& pl, char* ws, int64_t m, int64_t m_pad, float* Yin,
+                              float* Qf, void* Qt, int qt_dt, bf16* Ut, int64_t ldt, bool hilo, Launcher& L) {
+  const int64_t k = s.r;
+  float* gram_part = (float*)(ws + pl.off_gram_part);
+  float* gram = (float*)(ws + pl.off_gram);
+  float* rt = (float*)(ws + pl.off_rt);
+  float* W = Qf ? Qf : Yin;
+  const int nb = (int)ceil_div(k, kRsvdMaxRank);
+  auto rimg = [&](int j) { return (float*)(ws + pl.off_rinv + (size_t)j * kCholImageBytes); };
+  float* scale_ref = rimg(nb);  // behind the last image
+  {  // Gram = Yin^T . Yin, the row range split, partials folded in a fixed order
+    GemmParams g{};
+    g.A = Yin; g.B = Yin; g.C = gram_part;
+    g.M = k; g.N = k; g.K = m;
+    g.a_sm = 1; g.a_sk = k; g.b_sk = k; g.b_sn = 1; g.c_sm = k; g.c_sn = 1;
+    g.k_per_split = round_up(ceil_div(m, kGramSplitsBlocked), 32);
+    g.c_split_stride = k * k;
+    const int splits = (int)ceil_div(m, g.k_per_split);
+    launch_generic<float, float, float, float, false, true>(g, splits, L);
+    L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, splits, k * k, gram);
+    L(diag_max_kernel, dim3(1), dim3(64), (const float*)gram, (int)k, k, scale_ref);
+  }
+  for (int j = 0; j < nb; ++j) {
+    const int64_t jb = (int64_t)j * kRsvdMaxRank;
+    const int64_t w = k - jb < kRsvdMaxRank ? k - jb : kRsvdMaxRank, rest = k - jb - w;
+    L(chol_factor_kernel<64>, dim3(1), dim3(64), (const float*)(gram + jb * k + jb), rimg(j), (int)w, k,
+      (const float*)scale_ref, (float)k * 1.1920929e-7f);
+    if (rest == 0) break;
+    // Rt[rows below, block column j] = G[rows below, block column j] . R_jj^-1  (= the row panel of R, transposed)
+    L(tall_solve_kernel<64, float>, dim3((unsigned)ceil_div(rest, 64)), dim3(64), (const float*)(gram + (jb + w) * k + jb),
+      rest, (int)w, (const float*)rimg(j), rt + (jb + w) * k + jb, (float*)nullptr, (bf16*)nullptr, (int64_t)0, rest, 0, k,
+      k, 0);
+    GemmParams u{};  // trailing block -= panel^T . panel, both triangles (the panels below read the lower one)
+    u.A = rt + (jb + w) * k + jb; u.B = u.A; u.C = gram + (jb + w) * k + (jb + w);
+    u.M = rest; u.N = rest; u.K = w;
+    u.a_sm = k; u.a_sk = 1; u.b_sk = 1; u.b_sn = k; u.c_sm = k; u.c_sn = 1;
+    u.k_per_split = round_up(w, 32);
+    u.accumulate = 1; u.alpha = -1.f; u.beta = 1.f;
+    launch_generic<float, float, float, float, false, true>(u, 1, L);
+  }
+  const int64_t rows_out = Ut ? m_pad : m;
+  const int hl = hilo ? 1 : 0;
+  for (int j = 0; j < nb; ++j) {
+    const int64_t jb = (int64_t)j * kRsvdMaxRank;
+    const int64_t w = k - jb < kRsvdMaxRank ? k - jb : kRsvdMaxRank;
+    if (j > 0) {  // Y_j -= Q_{<j} . R_{<j, j};  R[t][jb + c] = Rt[(jb + c) * k + t]
+      GemmParams u{};
+      u.A = W; u.B = rt + jb * k; u.C = Yin + jb;
+      u.M = m; u.N = w; u.K = jb;
+      u.a_sm = k; u.a_sk = 1; u.b_sk = 1; u.b_sn = k; u.c_sm = k; u.c_sn = 1;
+      u.k_per_split = round_up(jb, 32);
+      u.accumulate = 1; u.alpha = -1.f; u.beta = 1.f;
+      launch_generic<float, float, float, float, false, true>(u, 1, L);
+    }
+    const dim3 grid((unsigned)ceil_div(rows_out, 64));
+    bf16* ut_j = Ut ? Ut + jb * ldt : nullptr;
+    if (qt_dt == ACC_BF16)
+      L(tall_solve_kernel<64, bf16>, grid, dim3(64), (const float*)(Yin + jb), m, (int)w, (const float*)rimg(j), W + jb,
+        Qt ? (bf16*)Qt + jb : (bf16*)nullptr, ut_j, ldt, rows_out, hl, k, k, (int)k);
+    else
+      L(tall_solve_kernel<64, float>, grid, dim3(64), (const float*)(Yin + jb), m, (int)w, (const float*)rimg(j), W + jb,
+        Qt ? (float*)Qt + jb : (float*)nullptr, ut_j, ldt, rows_out, hl, k, k, (int)k);
+  }
+}
+
 // One Cholesky-QR pass on a tall matrix Yin [m, k] fp32: Q = Yin . R^-1 with Yin^T.Yin = R^T.R.  Q goes to any
 // of: Qf (fp32 [m, k]), Qt (factor dtype [m, k]), Ut (bf16 [k, ldt] zero-padded transpose up to column
-// m_pad; [2k, ldt] hi / lo parts with `hilo`).
-void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, int64_t m, int64_t m_pad, const float* Yin,
+// m_pad; [2k, ldt] hi / lo parts with `hilo`).  Ranks above 64 take the blocked form, which overwrites Yin.
+void cholesky_qr_pass(const Shape& s, const RsvdPlan& pl, char* ws, int64_t m, int64_t m_pad, float* Yin,
                       float* Qf, void* Qt, int qt_dt, bf16* Ut, int64_t ldt, bool hilo, Launcher& L) {
   const int64_t k = s.r;
+  if (k > kRsvdMaxRank) {
+    cholesky_qr_pass_blocked(s, pl, ws, m, m_pad, Yin, Qf, Qt, qt_dt, Ut, ldt, hilo, L);
+    return;
+  }
   float* gram_part = (float*)(ws + pl.off_gram_part);
   float* rinv = (float*)(ws + pl.off_rinv);
   float* gram = (float*)(ws + pl.off_gram);
   const int rows = (int)round_up(ceil_div(m, pl.g_gram), 64);
   const int parts = (int)ceil_div(m, rows);
-  L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), Yin, m, (int)k, rows, gram_part);
+  L(gram_partial_kernel, dim3((unsigned)parts), dim3(256), (const float*)Yin, m, (int)k, rows, gram_part);
   L(sum_parts_kernel, dim3((unsigned)ceil_div(k * k, 64)), dim3(1024), (const float*)gram_part, parts, k * k, gram);
-  if (k <= 32) L(chol_factor_kernel<32>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
-  else L(chol_factor_kernel<64>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k);
+  if (k <= 32) L(chol_factor_kernel<32>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k, k, (const float*)nullptr, 1e-6f);
+  else L(chol_factor_kernel<64>, dim3(1), dim3(64), (const float*)gram, rinv, (int)k, k, (const float*)nullptr, 1e-6f);
   const int64_t rows_out = Ut ? m_pad : m;
   const dim3 grid((unsigned)ceil_div(rows_out, 64));
   const int hl = hilo ? 1 : 0;
   if (k <= 32) {
     if (qt_dt == ACC_BF16)
-      L(tall_solve_kernel<32, bf16>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
-        (bf16*)Qt, Ut, ldt, rows_out, hl);
+      L(tall_solve_kernel<32, bf16>, grid, dim3(64), (const float*)Yin, m, (int)k, (const float*)rinv, Qf,
+        (bf16*)Qt, Ut, ldt, rows_out, hl, k, k, (int)k);
     else
-      L(tall_solve_kernel<32, float>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
-        (float*)Qt, Ut, ldt, rows_out, hl);
+      L(tall_solve_kernel<32, float>, grid, dim3(64), (const float*)Yin, m, (int)k, (const float*)rinv, Qf,
+        (float*)Qt, Ut, ldt, rows_out, hl, k, k, (int)k);
   } else {
     if (qt_dt == ACC_BF16)
-      L(tall_solve_kernel<64, bf16>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
-        (bf16*)Qt, Ut, ldt, rows_out, hl);
+      L(tall_solve_kernel<64, bf16>, grid, dim3(64), (const float*)Yin, m, (int)k, (const float*)rinv, Qf,
+        (bf16*)Qt, Ut, ldt, rows_out, hl, k, k, (int)k);
     else
-      L(tall_solve_kernel<64, float>, grid, dim3(64), Yin, m, (int)k, (const float*)rinv, Qf,
-        (float*)Qt, Ut, ldt, rows_out, hl);
+      L(tall_solve_kernel<64, float>, grid, dim3(64), (const float*)Yin, m, (int)k, (const float*)rinv, Qf,
+        (float*)Qt, Ut, ldt, rows_out, hl, k, k, (int)k);
   }
 }
 
@@ -694,7 +790,7 @@ int validate_rsvd(const acc_linear_desc* d, Shape* s) {
   if (rc != ACC_OK) return rc;
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH)) return ACC_ERR_INVALID_ARG;
   if (s->ldf != s->r) return ACC_ERR_SHAPE;  // the RSVD factors are dense
-  if (s->r > kRsvdMaxRank || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
+  if (s->r > kRsvdMaxRankBlocked || s->n < s->r || s->d_in < s->r) return ACC_ERR_SHAPE;
   return ACC_OK;
 }
 
@@ -707,7 +803,7 @@ int validate_lowrank(const acc_linear_desc* d, Shape* s, int64_t k, bool for_pro
   if (d->flags & (ACC_FLAG_SKIP_SKETCH | ACC_FLAG_ONE_LAUNCH | ACC_FLAG_DW_ACCUMULATE)) return ACC_ERR_INVALID_ARG;
   if (s->ldf != s->r) return ACC_ERR_SHAPE;  // the optimizer calls read dense factors
   if (k < 0 || k % 8 || k > s->d_in || k > (1 << 16)) return ACC_ERR_SHAPE;
-  if (for_projector && (k < 8 || k > kRsvdMaxRank || k > s->r)) return ACC_ERR_SHAPE;
+  if (for_projector && (k < 8 || k > kRsvdMaxRankBlocked || k > s->r)) return ACC_ERR_SHAPE;
   return ACC_OK;
 }
 
@@ -715,7 +811,7 @@ struct LowrankPlan {
   int t1_splits, z_splits, g_gram;
   int64_t t1_k_per_split, z_k_per_split;
   size_t off_n, off_part, off_t1, off_r;                                  // the step
-  size_t off_z, off_yp, off_q1, off_gram_part, off_gram, off_rinv;        // the projector (shares off_part)
+  size_t off_z, off_yp, off_q1, off_gram_part, off_gram, off_rinv, off_rt;  // the projector (shares off_part)
   size_t step_total, total;
 };
 
@@ -749,14 +845,13 @@ LowrankPlan plan_lowrank(const acc_linear_desc* d, const Shape& s, int64_t k) {
   pl.off_t1 = take((size_t)k * s.r * 4);
   pl.off_r = take((size_t)k * s.d_out * 4);
   pl.step_total = off;
-  if (k <= kRsvdMaxRank && k <= s.r) {
+  if (k <= kRsvdMaxRankBlocked && k <= s.r) {
     pl.g_gram = 256;
     pl.off_z = take((size_t)s.r * k * 4);
     pl.off_yp = take((size_t)s.d_in * k * 4);
     pl.off_q1 = take((size_t)s.d_in * k * 4);
-    pl.off_gram_part = take((size_t)pl.g_gram * k * k * 4);
-    pl.off_gram = take((size_t)k * k * 4);
-    pl.off_rinv = take(kCholImageBytes);
+    const QrScratch q = take_qr_scratch(k, pl.g_gram, take);
+    pl.off_gram_part = q.gram_part; pl.off_gram = q.gram; pl.off_rinv = q.rinv; pl.off_rt = q.rt;
   }
   pl.total = off;
   return pl;
@@ -1114,6 +1209,7 @@ int acc_lowrank_projector(const acc_linear_desc* desc, int64_t k, const void* le
   sk.r = k;
   RsvdPlan rp{};
   rp.g_gram = pl.g_gram; rp.off_gram_part = pl.off_gram_part; rp.off_gram = pl.off_gram; rp.off_rinv = pl.off_rinv;
+  rp.off_rt = pl.off_rt;
   cholesky_qr_pass(sk, rp, ws, s.d_in, s.d_in, yp, q1, nullptr, ACC_F32, nullptr, 0, false, L);
   cholesky_qr_pass(sk, rp, ws, s.d_in, s.d_in, q1, nullptr, P, desc->factor_dtype, nullptr, 0, false, L);
   return L.status();

@@ -8,7 +8,8 @@
 
 namespace acc {
 
-constexpr int kRsvdMaxRank = 64;   // the k x k factorisation runs on one wave, one matrix row per lane
+constexpr int kRsvdMaxRank = 64;   // a k x k factorisation of this size runs on one wave, one matrix row per lane
+constexpr int kRsvdMaxRankBlocked = 512;  // larger ranks: the same kernels on 64 x 64 diagonal blocks (blocked Cholesky)
 
 __device__ __forceinline__ float lane_bcast(float v, int src_lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
@@ -30,7 +31,13 @@ __device__ __forceinline__ float lane_bcast(float v, int src_lane) {
 // the span of the others is unchanged.
 template <int K>
 __global__ __launch_bounds__(64) void chol_factor_kernel(const float* __restrict__ G, float* __restrict__ Rimg,
-                                                         int k) {
+                                                         int k, int64_t ldg, const float* __restrict__ scale_ref,
+                                                         float rel_tol) {
+  // ldg: row stride of G.  scale_ref: when not null, the largest diagonal entry of the WHOLE matrix this block
+  // belongs to (blocked factorisation: a trailing block that is nothing but rounding noise must be measured against
+  // the matrix it came from, not against itself); null: the largest diagonal entry of G itself.  rel_tol: a pivot
+  // at or below rel_tol times that scale counts as zero (1e-6 for one block; the blocked form passes its rank
+  // times 2^-23, the size of the rounding noise that `rank` elimination steps leave on an exactly dependent column).
   __shared__ float rows[K][K + 1];
   __shared__ float scale[K];
   const int lane = threadIdx.x;
@@ -39,7 +46,7 @@ __global__ __launch_bounds__(64) void chol_factor_kernel(const float* __restrict
     const int lr = lane < k ? lane : k - 1;
 #pragma unroll
     for (int c = 0; c < K; ++c) {
-      const float g = G[lr * k + (c < k ? c : k - 1)];
+      const float g = G[lr * ldg + (c < k ? c : k - 1)];
       a[c] = (lane < k && c < k) ? g : (lane == c ? 1.f : 0.f);
     }
   }
@@ -52,7 +59,7 @@ __global__ __launch_bounds__(64) void chol_factor_kernel(const float* __restrict
     const float d = lane_bcast(diag, l);
     maxdiag = d > maxdiag ? d : maxdiag;
   }
-  const float tol = maxdiag * 1e-6f;
+  const float tol = (scale_ref ? *scale_ref : maxdiag) * rel_tol;
   float my_piv = 0.f;   // pivot of my row, 0 for a dropped one
   __shared__ __attribute__((aligned(16))) float bc[2][K];   // the pivot row of a step, for all lanes to read
 #pragma unroll 1
@@ -110,6 +117,22 @@ __global__ __launch_bounds__(64) void chol_factor_kernel(const float* __restrict
   }
 }
 
+// out[0] = the largest diagonal entry of the symmetric matrix G [k, k] (row stride ldg).  One wave.
+__global__ __launch_bounds__(64) void diag_max_kernel(const float* __restrict__ G, int k, int64_t ldg,
+                                                      float* __restrict__ out) {
+  float m = 0.f;
+  for (int i = threadIdx.x; i < k; i += 64) {
+    const float d = G[i * ldg + i];
+    m = d > m ? d : m;
+  }
+#pragma unroll
+  for (int l = 0; l < 64; ++l) {
+    const float d = lane_bcast(m, l);
+    if (threadIdx.x == 0 && l > 0) m = d > m ? d : m;
+  }
+  if (threadIdx.x == 0) out[0] = m;
+}
+
 // Q = Y . R^-1 for a tall Y [n, k] fp32 by forward substitution along each row, q_c = (y_c - sum_{t<c} q_t
 // R[t][c]) / R[c][c]: one row per lane, the row in registers, R read from LDS (all lanes read the same address).
 // No explicit inverse is formed.  Columns are taken eight at a time in a rolled loop: substitution inside the
@@ -127,7 +150,10 @@ template <int K, typename TU>
 __global__ __launch_bounds__(64) void tall_solve_kernel(const float* __restrict__ Y, int64_t n, int k,
                                                         const float* __restrict__ Rimg, float* __restrict__ Qf,
                                                         TU* __restrict__ Qt, bf16* __restrict__ Ut, int64_t ldt,
-                                                        int64_t n_rows_out, int hilo) {
+                                                        int64_t n_rows_out, int hilo, int64_t ldy, int64_t ldq,
+                                                        int lo_rows) {
+  // ldy: row stride of Y; ldq: row stride of Qf and Qt (a column block of a wider matrix passes the wide stride);
+  // lo_rows: row of Ut where the lo parts start (the full rank when this call handles one column block)
   // Rs[t * K + c] = R[t][c] for t < c < k, zero elsewhere; one spare row: the update of the last columns reads
   // up to K - 9 elements past a row's end
   __shared__ __attribute__((aligned(16))) float Rs[K * K + 2 * K];
@@ -152,7 +178,7 @@ __global__ __launch_bounds__(64) void tall_solve_kernel(const float* __restrict_
 #pragma unroll
   for (int c = 0; c < K; c += 4) {
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
-    if (row < n && c < k) v = *(const f32x4*)(Y + row * k + c);
+    if (row < n && c < k) v = *(const f32x4*)(Y + row * ldy + c);
 #pragma unroll
     for (int t = 0; t < 4; ++t) y[c + t] = v[t];
   }
@@ -190,18 +216,18 @@ __global__ __launch_bounds__(64) void tall_solve_kernel(const float* __restrict_
     }
     if (row < n) {
       if (Qf) {
-        *(f32x4*)(Qf + row * k + cb) = f32x4{q[0], q[1], q[2], q[3]};
-        *(f32x4*)(Qf + row * k + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
+        *(f32x4*)(Qf + row * ldq + cb) = f32x4{q[0], q[1], q[2], q[3]};
+        *(f32x4*)(Qf + row * ldq + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
       }
       if (Qt) {
         if constexpr (sizeof(TU) == 2) {
           bf16x8 o;
 #pragma unroll
           for (int t = 0; t < 8; ++t) o[t] = (bf16)q[t];
-          *(bf16x8*)(Qt + row * k + cb) = o;
+          *(bf16x8*)(Qt + row * ldq + cb) = o;
         } else {
-          *(f32x4*)(Qt + row * k + cb) = f32x4{q[0], q[1], q[2], q[3]};
-          *(f32x4*)(Qt + row * k + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
+          *(f32x4*)(Qt + row * ldq + cb) = f32x4{q[0], q[1], q[2], q[3]};
+          *(f32x4*)(Qt + row * ldq + cb + 4) = f32x4{q[4], q[5], q[6], q[7]};
         }
       }
     }
@@ -210,7 +236,7 @@ __global__ __launch_bounds__(64) void tall_solve_kernel(const float* __restrict_
       for (int jj = 0; jj < 8; ++jj) {
         const bf16 hi = row < n ? (bf16)q[jj] : (bf16)0.f;
         Ut[(int64_t)(cb + jj) * ldt + row] = hi;
-        if (hilo) Ut[(int64_t)(k + cb + jj) * ldt + row] = row < n ? (bf16)(q[jj] - (float)hi) : (bf16)0.f;
+        if (hilo) Ut[(int64_t)(lo_rows + cb + jj) * ldt + row] = row < n ? (bf16)(q[jj] - (float)hi) : (bf16)0.f;
       }
     }
 #pragma unroll

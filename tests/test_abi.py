@@ -140,8 +140,11 @@ def test_rsvd_entry_points_validate_the_rank():
     args = (0x1000, 0x2000, 0x3000, 0x4000, 0x6000, 0x5000, 1 << 40, None)
     ok = dict(n=256, d_in=256, d_out=512)
     assert f(ctypes.byref(acc.make_desc(**ok, r=8)), *args) in (0, -6)
-    for bad_r in (4, 12, 72, 128, 256):
-        assert f(ctypes.byref(acc.make_desc(**ok, r=bad_r)), *args) == -2, bad_r
+    for bad_r in (4, 12, 520, 1024):     # not a multiple of 8, above the limit of 512
+        assert f(ctypes.byref(acc.make_desc(n=2048, d_in=2048, d_out=512, r=bad_r)), *args) == -2, bad_r
+    for good_r in (72, 128, 256):        # ranks above 64 run the blocked factorisation
+        assert f(ctypes.byref(acc.make_desc(**ok, r=good_r)), *args) in (0, -6), good_r
+    assert f(ctypes.byref(acc.make_desc(**ok, r=512)), *args) == -2                          # n, d_in < rank
     assert f(ctypes.byref(acc.make_desc(n=16, d_in=256, d_out=512, r=32)), *args) == -2      # n < rank
     assert f(ctypes.byref(acc.make_desc(**ok, r=16, flags=acc.ACC_FLAG_SKIP_SKETCH)), *args) == -1
     d = acc.make_desc(**ok, r=16)
@@ -149,7 +152,8 @@ def test_rsvd_entry_points_validate_the_rank():
     assert need > 0 and acc.acc_rsvd_workspace_bytes(d, True) > 0
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, 0x4000, 0x6000, 0x5000, need - 1, None) == -5
     assert f(ctypes.byref(d), 0x1000, 0x2000, 0x3000, None, 0x6000, 0x5000, need, None) == -1
-    assert acc.acc_rsvd_workspace_bytes(acc.make_desc(**ok, r=72), False) == 0
+    assert acc.acc_rsvd_workspace_bytes(acc.make_desc(**ok, r=72), False) > need
+    assert acc.acc_rsvd_workspace_bytes(acc.make_desc(n=2048, d_in=2048, d_out=512, r=520), False) == 0
 
 
 def test_flag_constants_match_the_header():
@@ -204,8 +208,11 @@ def test_lowrank_optimizer_entry_points_validate_their_arguments():
 
     assert call_proj() in (0, -6)
     assert call_proj(left=None) == -1 and call_proj(Gr=None) == -1 and call_proj(P=None) == -1
-    for k in (0, 4, 72, 128):      # below 8, not a multiple of 8, above r = 64 / the rank limit
+    for k in (0, 4, 72, 128):      # below 8, not a multiple of 8, above r = 64
         assert call_proj(k=k) == -2, k
+    d512 = acc.make_desc(n=256, d_in=1024, d_out=1024, r=640)
+    assert proj(ctypes.byref(d512), 128, 0x1000, 0x2000, 0x7000, 0x5000, big, None) in (0, -6)   # blocked factorisation
+    assert proj(ctypes.byref(d512), 520, 0x1000, 0x2000, 0x7000, 0x5000, big, None) == -2        # above the limit of 512
     assert call_proj(ws_bytes=need - 1) == -5 and call_proj(P=0x7002) == -3
     assert ctypes.sizeof(acc.AccAdamwHyper) == 32
 

@@ -123,7 +123,8 @@ def test_projected_three_steps(acc, flags_name, dtype, k, w_tol, step_tol):
 
 
 @pytest.mark.parametrize("flags_name", ["default", "w_out_in"])
-@pytest.mark.parametrize("dtype,k", [("f32", 8), ("f32", 40), ("bf16", 32), ("bf16", 64)])
+@pytest.mark.parametrize("dtype,k", [("f32", 8), ("f32", 40), ("bf16", 32), ("bf16", 64),
+                                     ("f32", 72), ("bf16", 128)])   # above 64: the blocked factorisation
 def test_projector_matches_oracle(acc, flags_name, dtype, k):
     """P = orthonormal basis (positive-diagonal QR) of left . (Gr . Omega).  Tolerance: the basis inherits the
     conditioning of Yp, so the bar is cond(Yp) times the output type's (1e-5 float32, 1e-2 bfloat16 capped at
@@ -131,7 +132,7 @@ def test_projector_matches_oracle(acc, flags_name, dtype, k):
     import torch
     dev = "cuda:0"
     flags = acc.ACC_FLAG_W_OUT_IN if flags_name == "w_out_in" else 0
-    lin = inputs.Linear("opt.P." + dtype, 1024, 520, 328, 72, dtype=dtype, x_kind="plain")
+    lin = inputs.Linear("opt.P." + dtype, 1024, 520, 328, max(72, k + 8), dtype=dtype, x_kind="plain")
     code = acc.ACC_BF16 if dtype == "bf16" else acc.ACC_F32
     left_h, (gr_h,) = inputs.make_gradient_factors(lin, 1)
     left = acc.to_device(left_h, dev)

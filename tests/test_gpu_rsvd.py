@@ -93,6 +93,12 @@ SHAPES = [
     (2049, 1032, 1544, 64, "bf16"),     # largest rank, ragged everything (generic kernels: d_in % 64 != 0)
     (3001, 1024, 1544, 48, "bf16"),     # rank padded to 64 inside the kernels, split-K path, ragged token count
     (16384, 3072, 3072, 32, "bf16"),    # the 3B-shaped projection at the paper's rank
+    # ranks above 64: the blocked Cholesky QR on 64 x 64 diagonal blocks
+    (700, 264, 136, 72, "f32"),         # one full block and a ragged one of 8, generic kernels, float32
+    (1030, 520, 264, 128, "bf16"),      # two blocks, generic kernels
+    (4100, 1024, 1544, 192, "bf16"),    # three blocks, split-K path, ragged tokens
+    (4096, 1024, 1024, 256, "bf16"),    # the rank of the 3B-shaped configurations
+    (16384, 3072, 3072, 256, "bf16"),   # the 3B-shaped projection at its own sketch rank
 ]
 
 
@@ -145,6 +151,24 @@ def test_rsvd_is_exact_for_low_rank_inputs_and_drops_dependent_columns(acc):
     assert zero_cols == k - 12, zero_cols
 
 
+def test_rsvd_blocked_rank_drops_dependent_columns(acc):
+    """rank(X) = 40 < k = 96 (two diagonal blocks): the surplus basis vectors come out as zero in both blocks and
+    U.V^T still reproduces X."""
+    rng = np.random.default_rng(11)
+    n, d_in, d_out, k = 900, 256, 96, 96
+    X = (rng.standard_normal((n, 40)) @ rng.standard_normal((40, d_in))).astype(np.float32)
+    lin = inputs.Linear("rsvd_lowrank_blocked", n, d_in, d_out, k, dtype="f32", seed=1)
+    data = inputs.make(lin)
+    data["X"] = X
+    got = run_rsvd(acc, lin, data)
+    Xf, dYf = X.astype(np.float64), inputs.as_f64(data["dY"])
+    assert np.all(np.isfinite(got["U"])) and np.all(np.isfinite(got["V"]))
+    assert gu.rel(got["U"] @ got["V"].T, Xf) <= 1e-4
+    assert gu.rel(got["dW"], Xf.T @ dYf) <= 1e-4
+    zero_cols = int(np.sum(np.linalg.norm(got["U"], axis=0) == 0))
+    assert zero_cols == k - 40, zero_cols
+
+
 def test_rsvd_is_deterministic_and_seed_dependent(acc):
     lin = inputs.Linear("rsvd_det", 900, 256, 128, 16, dtype="bf16", seed=5)
     data = inputs.make(lin)
@@ -172,6 +196,8 @@ def test_rsvd_strided_operands_and_accumulated_gradient(acc, n, d_in, d_out, k):
 
 
 @pytest.mark.parametrize("n,d_in,d_out,k,dtype,q", [
+    (1030, 520, 264, 128, "bf16", 1),    # blocked Cholesky QR (two blocks), generic kernels
+    (4100, 1024, 1544, 192, "bf16", 2),  # blocked (three blocks), split-K path with hi / lo parts
     (515, 264, 136, 8, "f32", 1),        # generic kernels, float32
     (777, 520, 264, 32, "bf16", 2),      # generic kernels, bfloat16
     (1000, 512, 640, 8, "bf16", 1),      # split-K path
