@@ -267,21 +267,15 @@ void fast_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, int6
     p.red_row = job->row; p.red_ld = job->ld;
   }
   const int64_t big_tiles = ceil_div(M, 256) * ceil_div(N, 256);
-  if (big_tiles >= 192) {  // 256 x 256 tiles: enough tiles to fill 256 CUs.  4 waves of 128 x 128 read a third
-                           // fewer operand bytes from LDS per flop than 8 waves of 128 x 64: +0.4 % on a step
-    const unsigned grid = gemm_bf16_plan(p, 256, 256);
+  if (big_tiles >= 192) {  // 256 x 256 tiles: enough tiles to fill 256 CUs
+    const unsigned grid = gemm_bf16_plan(p, 256, 256);  // a multiple of 256 slots
     p.red_stride = (int64_t)grid * 256 * 4;
     if constexpr (sizeof(TC) == 2) {
-      if (!accumulate && grid >= 256 && K >= 192) {
+      if (!accumulate && K >= 192) {
         // 256 persistent work-groups on the 16x16x32 instruction; one round of tiles takes it too (a 3072 -> 1024
         // projection: GEMM 84.3 against 86.4 us on the 32x32x16 kernel below)
         p.red_stride = (int64_t)256 * 256 * 4;
         L.launch_lds(gemm16_persist_kernel<KMAJ>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)grid);
-        return;
-      }
-      if (!accumulate) {  // the epilogue folded into the last K tile
-        L.launch_lds(gemm_bf16_kernel<2, 2, 4, 4, KMAJ, TC, true>, dim3(grid), dim3(256),
-                     (size_t)gemm_bf16_lds_bytes<2, 2, 4, 4>(), p);
         return;
       }
     }

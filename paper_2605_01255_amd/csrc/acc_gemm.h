@@ -127,8 +127,7 @@ __device__ __forceinline__ bool xcd_tile(const FastGemmParams& p, int b, int& tm
 }
 
 // The work of one work-group: output tile number b (see xcd_tile), using the dynamic LDS at smem.
-// FOLD: the epilogue runs inside the last K tile (4 x 4 blocks per wave, bf16 output, no accumulation into C).
-template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, bool FOLD = false>
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC>
 __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, char* smem) {
   constexpr int NW = WM * WN;
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64;
@@ -371,111 +370,6 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   int kt = 0;
   for (; kt + 2 < KT; ++kt) ktile(kt, std::true_type{});
 
-  // Last K tile of the big bf16 tile with the epilogue folded into it.  The 64 MFMAs run block row by block row
-  // (i), each in two halves of 64 output columns (jh): the 32 x 64 unit (i, jh) is final after its eight MFMAs
-  // and is converted, staged, read back and stored in the slots of the sixteen MFMAs that follow, so the matrix
-  // pipe works while the accumulators are read out (an epilogue after the loop is all issue and LDS latency
-  // with the pipe idle: 8 % of the kernel).  Staging uses the stage the pipeline no longer needs (every wave
-  // passed the previous tile's barrier, nothing is in flight), two private regions per wave, so no barrier.
-  if constexpr (FOLD) {
-    static_assert(TM == 4 && TN == 4 && sizeof(TC) == 2, "folded epilogue: 4 x 4 blocks per wave, bf16 output");
-    {
-      for (; kt + 1 < KT; ++kt) ktile(kt, std::false_type{});
-      const char* cur = smem + (kt & 1) * STAGE;
-      constexpr int UPITCH = 64 * 2 + 8;   // 64 staged columns + 2 banks: 32 rows on distinct banks
-      constexpr int UNIT_B = 32 * UPITCH;
-      static_assert(NW * 2 * UNIT_B <= STAGE, "staging regions exceed the idle stage");
-      char* region = smem + ((kt + 1) & 1) * STAGE + wave * (2 * UNIT_B);
-      TC* __restrict__ C = (TC*)p.C + (int64_t)split * p.c_split_stride;
-      const int64_t gm_base = m0 + wm * TM * 32, gn_base = n0 + wn * TN * 32;
-      int64_t c_rows = p.M - gm_base;
-      if (c_rows > TM * 32) c_rows = TM * 32;
-      const int64_t c_bytes = (c_rows > 0 && gn_base < p.N) ? ((c_rows - 1) * p.ldc + (p.N - gn_base)) * 2 : 0;
-      const __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc(
-          (void*)(C + gm_base * p.ldc + gn_base), 0, (int)(uint32_t)c_bytes, 0x00020000);
-      // read-back t of a unit: row 8 * t + lane / 8, 16-byte chunk lane % 8 (8 columns)
-      const int e_row = lane >> 3, e_ch = lane & 7;
-      uint32_t c_voff[2];
-#pragma unroll
-      for (int jh = 0; jh < 2; ++jh)
-        c_voff[jh] = gn_base + jh * 64 + e_ch * 8 < p.N ? (uint32_t)((e_row * p.ldc + jh * 64 + e_ch * 8) * 2)
-                                                        : 0xFFFFFFF0u;  // columns past N: out of range, dropped
-      const uint32_t c_row_bytes = (uint32_t)(p.ldc * 2);
-      char* const w_base = region + lrow * UPITCH + kg * 8;
-      const char* const r_base = region + e_row * UPITCH + e_ch * 16;
-      auto wave_fence = [&]() {  // lanes read what other lanes of the wave wrote: keep the compiler's order
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      };
-      // unit u = 2 * i + jh; staging write k of a unit: block column jj = k / 4, register group g4 = k % 4
-      auto stage_write = [&](int u, int k) {
-        const int i = u >> 1, j = 2 * (u & 1) + (k >> 2), g4 = k & 3;
-        bf16x4 v;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] = (bf16)acc[i][j][g4 * 4 + t];
-        *(bf16x4*)(w_base + (u & 1) * UNIT_B + ((k >> 2) * 32 + g4 * 8) * 2) = v;
-      };
-      auto read_back = [&](int u, int t) -> u32x4 {
-        return *(const u32x4*)(r_base + (u & 1) * UNIT_B + t * 8 * UPITCH);
-      };
-      auto store_back = [&](int u, int t, u32x4 v) {
-        const uint32_t soff = (uint32_t)((u >> 1) * 32 + t * 8) * c_row_bytes;
-        __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff[u & 1], soff, 0);
-      };
-
-      // A operands: k-step 0 of every block row is in af[0]; k-steps 1 .. 3 of block row i sit in aq[i & 1],
-      // those of row i + 1 are read while row i is multiplied.  B operands of all four k-steps stay in bq.
-      auto a_frag = [&](int ks, int i) -> bf16x8 {
-        return lds_read_b128(cur, a_rd[i] + (((2 * ks + kg) ^ a_swz) << 4));
-      };
-      bf16x8 aq[2][4], bq[4][TN];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bq[0][j] = bfr[0][j];
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int ks = 1; ks < 4; ++ks) {  // what the first eight MFMAs need beyond k-step 0
-        aq[0][ks] = a_frag(ks, 0);
-        read_b1(cur, ks, 0, bq[ks]);
-        read_b1(cur, ks, 1, bq[ks]);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      u32x4 back[4];
-#pragma unroll
-      for (int h = 0; h < 8; ++h) {
-        const int i = h >> 1, jh = h & 1;
-        if (h >= 2) wave_fence();  // unit h - 2 is staged completely (writes issued in the slots of unit h - 1)
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const int ks = k >> 1, j = 2 * jh + (k & 1);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bq[ks][j], ks == 0 ? af[0][i] : aq[i & 1][ks],
-                                                              acc[i][j], 0, 0, 0);
-          // operands of the later MFMAs, in the order they are needed
-          if (h == 0 && k < 6) read_b1(cur, 1 + k / 2, 2 + (k & 1), bq[1 + k / 2]);
-          if (jh == 0 && i < 3 && k >= 5) aq[(i + 1) & 1][k - 4] = a_frag(k - 4, i + 1);
-          // read-out of the units that are final
-          if (h >= 1) stage_write(h - 1, k);
-          if (h >= 2 && k < 4) back[k] = read_back(h - 2, k);
-          if (h >= 2 && k >= 4) store_back(h - 2, k - 4, back[k - 4]);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-      // drain: unit 7 is staged, units 6 and 7 are read back and stored
-      u32x4 back7[4];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) stage_write(7, k);
-      wave_fence();
-#pragma unroll
-      for (int t = 0; t < 4; ++t) back[t] = read_back(6, t);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) back7[t] = read_back(7, t);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) store_back(6, t, back[t]);
-#pragma unroll
-      for (int t = 0; t < 4; ++t) store_back(7, t, back7[t]);
-      return;
-    }
-  }
   for (; kt < KT; ++kt) ktile(kt, std::false_type{});
 
   // ---- epilogue ----
@@ -538,10 +432,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const FastGemmParams& p, int b, c
   }
 }
 
-template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC, bool FOLD = false>
+template <int WM, int WN, int TM, int TN, bool B_KMAJOR, typename TC>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_bf16_kernel(FastGemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  gemm_bf16_tile<WM, WN, TM, TN, B_KMAJOR, TC, FOLD>(p, blockIdx.x, smem);
+  gemm_bf16_tile<WM, WN, TM, TN, B_KMAJOR, TC>(p, blockIdx.x, smem);
 }
 
 template <int WM, int WN, int TM, int TN>
