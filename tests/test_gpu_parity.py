@@ -190,6 +190,28 @@ def test_persistent_gemm_across_output_tiles(acc, n, d_in, d_out, r, pad):
     _check(acc, inputs.Linear(f"persist_{n}x{d_in}x{d_out}", n, d_in, d_out, r, dtype="bf16"), pad=pad)
 
 
+def _seeded_big_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        n = int(rng.integers(3000, 9000))
+        d_in = 8 * int(rng.integers(24, 160))        # 192 ... 1272; K % 64 != 0 takes the generic kernels
+        d_out = 8 * int(rng.integers(380, 640))      # 3040 ... 5112
+        if rng.integers(0, 3):
+            d_in = 64 * max(3, d_in // 64)           # mostly multiples of 64: the tuned kernels
+        r = int(rng.choice([16, 32, 64, 128, 192, 256]))
+        if -(-n // 256) * -(-d_out // 256) >= 192:
+            out.append((n, d_in, d_out, r))
+    return out
+
+
+@pytest.mark.parametrize("n,d_in,d_out,r", _seeded_big_shapes(6, 2024))
+def test_seeded_random_shapes_on_the_large_tile_kernels(acc, n, d_in, d_out, r):
+    """Seeded random sizes with at least 192 output tiles of 256 x 256 in the forward product (ragged in every
+    dimension): whatever kernels the planner picks, every output meets the full bar."""
+    _check(acc, inputs.Linear(f"rand_{n}x{d_in}x{d_out}_r{r}", n, d_in, d_out, r, dtype="bf16"))
+
+
 def test_one_launch_flag_gives_identical_results(acc):
     """ACC_FLAG_ONE_LAUNCH interleaves GEMM and sketch work-groups in one grid: same outputs, bit for bit
     for the exact products, within tolerance of the oracle for the factors."""
