@@ -1,4 +1,4 @@
-// bf16 GEMM on the 16x16x32 matrix instruction for shapes with several rounds of 256 x 256 output tiles
+// bf16 GEMM on the 16x16x32 matrix instruction for shapes with at least 192 output tiles of 256 x 256
 // (steps F1, B1):  C[M, N] = A[M, K] . B, fp32 accumulate, bf16 output.
 //
 //   A is row-major with K contiguous (X, dY).
@@ -20,8 +20,8 @@
 // One K tile = 128 slots (one matrix instruction each, at most a few other instructions beside it):
 //   slots   0 ..  63  k-step 0; the A / B operands of k-step 1 are read from the same stage; the last four
 //                     wave-loads of the next K tile go out (slots 2, 6, 10, 14)
-//   slots  64 .. 127  k-step 1; before slot 64 + BAR_Q the barrier (next K tile landed for every wave, every wave
-//                     done reading this stage); after it the operands of the next K tile's k-step 0 are read and
+//   slots  64 .. 127  k-step 1; before slot 64 + BAR_Q = 72 the barrier (next K tile landed for every wave, every
+//                     wave done reading this stage); after it the operands of the next K tile's k-step 0 are read and
 //                     the first twelve wave-loads of the K tile after next go into the stage just released, one
 //                     every four slots.  Every transfer then has 70 to 110 slots (1100 to 1800 clocks) to land.
 // Measured on the 3B-shaped projection (a step of the layer, same-box pairs): barrier before slot 72 0.547 - 0.552
@@ -31,8 +31,11 @@
 // behind each other), never do that.  Spreading the wave-loads evenly (nine after the barrier, one every six
 // slots, seven in the next k-step 0, one every six) 0.5545 against 0.5507; the last of them 14 slots before the
 // barrier instead of 58: 0.584 (the transfers need their thousand clocks to land).
-// Two waves per SIMD (eight waves of 128 x 64) run equal to four waves: what the second wave hides in issue
-// gaps it pays back in LDS operand reads (1.5 x).
+// What is left inside a K tile (in-kernel timestamps): 2924 clocks, of which the wait for the transfers is 8 and the
+// barrier 67; the matrix instructions alone need 2048 back to back, about 2380 at the rate one wave issues them, and
+// the rest is the issue of the sixteen 1 KB transfers per wave (a wave issues in order).  Two waves per SIMD (eight
+// waves of 128 x 64) hide that but read 1.5 x the operand bytes from LDS: equal in time.  Four consecutive wave-loads
+// sharing one LDS base in M0 through the instruction's immediate offset: correct, thirty times slower.
 #pragma once
 #include <type_traits>
 
@@ -44,9 +47,10 @@ namespace acc {
 // 16-column block at k rows 8 apart are sent to different 32-byte bank groups as well.
 __device__ __forceinline__ int swz_n16(int krow) { return ((krow & 3) << 2) | (((krow >> 3) & 1) << 1); }
 
-// Persistent form (256 work-groups walk over the output tiles b, b + 256, ...; see gemm_bf16_persist_kernel for the
-// idea): the K pipeline runs across output tiles and the read-out of a finished tile rides in the slots of the
-// matrix instructions that follow.
+// Persistent form: 256 work-groups (one per compute unit) walk over the output tiles b, b + 256, ...; the K pipeline
+// runs across output tiles and the read-out of a finished tile rides in the slots of the matrix instructions that
+// follow, so a new tile starts without a work-group launch, without a burst of first transfers from every compute
+// unit at once and without the matrix pipe idling during an epilogue.
 //   * K tile kt + 1 / kt + 2 of the slot program may belong to the next output tile: the transfers take their
 //     buffer resources from a per-K-tile choice between the current and the next tile's, the LDS side does not
 //     notice.  After the last output tile the "next" tile is the current one again: its first two K tiles are
