@@ -250,10 +250,10 @@ int acc_philox_dump_u32(uint64_t seed, uint64_t row_offset, int64_t n, int64_t r
  * Only n, r, seed, row_offset and io_dtype of desc are read. */
 int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream);
 
-/* Measurement hook: one launch of a loop of bf16 matrix instructions that touches only registers, 256
+/* Measurement hook: one launch of a loop of matrix instructions that touches only registers, 256
  * work-groups (one per compute unit) of 4 * waves_per_simd waves, each wave iters x 4 instructions on four
- * independent accumulator sets.  shape 0: 32x32x16, 1: 16x16x32; waves_per_simd 1 or 2; random_data 0: all
- * operands zero, 1: pseudo-random bf16 operands.  sink: device scratch of at least 256 * 256 * waves_per_simd
+ * independent accumulator sets.  shape 0: 32x32x16 bf16, 1: 16x16x32 bf16, 2: 16x16x128 fp8 (e4m3); waves_per_simd 1 or 2;
+ * random_data 0: all operands zero, 1: pseudo-random operands.  sink: device scratch of at least 256 * 256 * waves_per_simd
  * floats (overwritten); *flops (host) receives the flops of the launch.  Timing it (events, profiler) gives the
  * rate the matrix pipe sustains under the part's power limit, the practical ceiling of the MFMA-bound steps
  * (Def. 3.1's exact products).  1 <= iters <= 2^24. */

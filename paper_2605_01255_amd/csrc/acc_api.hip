@@ -1323,7 +1323,7 @@ int acc_sketch_dump(const acc_linear_desc* desc, float* S, void* stream) {
 int acc_probe_mfma(int shape, int waves_per_simd, int random_data, int64_t iters, float* sink, size_t sink_bytes,
                    double* flops, void* stream) {
   if (!sink || !flops) return ACC_ERR_INVALID_ARG;
-  if ((shape != 0 && shape != 1) || (waves_per_simd != 1 && waves_per_simd != 2) || iters < 1 || iters > (1 << 24))
+  if (shape < 0 || shape > 2 || (waves_per_simd != 1 && waves_per_simd != 2) || iters < 1 || iters > (1 << 24))
     return ACC_ERR_SHAPE;
   if (!aligned16(sink)) return ACC_ERR_ALIGN;
   const unsigned threads = 256u * (unsigned)waves_per_simd, groups = 256;  // one work-group per compute unit
@@ -1332,8 +1332,9 @@ int acc_probe_mfma(int shape, int waves_per_simd, int random_data, int64_t iters
   if (rc != ACC_OK) return rc;
   Launcher L{(hipStream_t)stream};
   if (shape == 0) L(mfma_probe_kernel<0>, dim3(groups), dim3(threads), random_data, iters, sink);
-  else L(mfma_probe_kernel<1>, dim3(groups), dim3(threads), random_data, iters, sink);
-  *flops = (double)groups * (threads / 64) * (double)iters * 4.0 * (shape == 0 ? 32768.0 : 16384.0);
+  else if (shape == 1) L(mfma_probe_kernel<1>, dim3(groups), dim3(threads), random_data, iters, sink);
+  else L(mfma_probe_kernel<2>, dim3(groups), dim3(threads), random_data, iters, sink);
+  *flops = (double)groups * (threads / 64) * (double)iters * 4.0 * (shape == 0 ? 32768.0 : shape == 1 ? 16384.0 : 65536.0);
   return L.status();
 }
 

@@ -272,7 +272,7 @@ def test_mfma_probe_hook_validates_arguments():
     big = 256 * 512 * 4
     assert f(0, 1, 0, 100, None, big, ctypes.byref(fl), None) == -1
     assert f(0, 1, 0, 100, 0x1000, big, None, None) == -1
-    assert f(2, 1, 0, 100, 0x1000, big, ctypes.byref(fl), None) == -2
+    assert f(3, 1, 0, 100, 0x1000, big, ctypes.byref(fl), None) == -2
     assert f(0, 3, 0, 100, 0x1000, big, ctypes.byref(fl), None) == -2
     assert f(0, 1, 0, 0, 0x1000, big, ctypes.byref(fl), None) == -2
     assert f(0, 1, 0, 100, 0x1004, big, ctypes.byref(fl), None) == -3
