@@ -150,6 +150,27 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
  * acc_lowrank_adamw_step take like any other; 2 M r (d_in + d_out) bytes are held instead of d_in d_out. */
 int acc_linear_dw(const acc_linear_desc* desc, const void* Xs, const void* Gr, void* dW, void* stream);
 
+/* The exact products on 8-bit floating-point operands (a widening of Def. 3.1's exact path; the paper itself
+ * computes in bf16): for callers that hold 8-bit copies of X, W and dY next to the bf16 tensors (the usual fp8
+ * training recipe: a cast with a per-tensor scale), F1 and B1 run on the fp8 matrix instructions, twice the bf16
+ * rate at half the operand bytes; everything else of the path (the sketches of the bf16 X and dY, the factors,
+ * the dense dW) is unchanged.
+ *   X8 [n, ldx], dY8 [n, ldy], W8 (shape and stride of W): one byte per element, OCP fp8 e4m3 (dY8 may be e5m2:
+ *   dy8_format); same strides, counted in elements, as their bf16 counterparts, but here ldx, ldw and ldy must be
+ *   multiples of 16.
+ *   Y  = scale * (X8 . W8)    (bf16, fp32 accumulation; scale = product of the two dequantisation scales)
+ *   dX = scale * (dY8 . W8^T)
+ * X / dY (bf16) are read by the sketch only (X and Xs may be NULL with ACC_FLAG_SKIP_SKETCH).  io_dtype must be
+ * ACC_BF16.  The contraction length (d_in forward, d_out backward) must be a multiple of 128 and at least 384,
+ * otherwise ACC_ERR_SHAPE: this path has no slower fall-back.  ACC_FLAG_ONE_LAUNCH is ignored.  Workspace as for
+ * acc_linear_fwd / acc_linear_bwd. */
+typedef enum { ACC_FP8_E4M3 = 0, ACC_FP8_E5M2 = 1 } acc_fp8_format;
+int acc_linear_fwd_fp8(const acc_linear_desc* desc, const void* X, const void* X8, const void* W8, float scale,
+                       void* Y, void* Xs, void* workspace, size_t ws_bytes, void* stream);
+int acc_linear_bwd_fp8(const acc_linear_desc* desc, const void* dY, const void* dY8, int dy8_format, const void* W8,
+                       float scale, const void* Xs, void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes,
+                       void* stream);
+
 /* Gradient of a bias b [d_out] that is broadcast over tokens (proof of Thm 3.2.2, bias term: the
  * gradient of the added term is grad_Z L itself, independent of X, hence exact under compression):
  * dB[o] = sum_i dY[i, o], accumulated in fp32 in a fixed order (bitwise reproducible), stored as

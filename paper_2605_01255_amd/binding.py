@@ -20,8 +20,10 @@ ACC_FLAG_DW_ACCUMULATE = 8
 ACC_FLAG_RSVD_POWER_SHIFT = 8   # flags bits 8..9: rounds of subspace iteration of the RSVD forward
 
 ACC_STATIC_SCRATCH_BYTES = 32 << 20
+ACC_FP8_E4M3, ACC_FP8_E5M2 = 0, 1
 
 EXPORTS = ("acc_linear_workspace_bytes", "acc_linear_fwd", "acc_linear_fwd_static", "acc_linear_bwd", "acc_linear_dw",
+           "acc_linear_fwd_fp8", "acc_linear_bwd_fp8",
            "acc_linear_bias_grad",
            "acc_rsvd_workspace_bytes", "acc_linear_fwd_rsvd", "acc_linear_bwd_rsvd", "acc_lowrank_workspace_bytes",
            "acc_lowrank_projector", "acc_lowrank_adamw_step",
@@ -69,6 +71,10 @@ _lib.acc_linear_fwd_static.restype = ctypes.c_int
 _lib.acc_linear_fwd_static.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp]
 _lib.acc_linear_bwd.restype = ctypes.c_int
 _lib.acc_linear_bwd.argtypes = [_dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_fwd_fp8.restype = ctypes.c_int
+_lib.acc_linear_fwd_fp8.argtypes = [_dp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _sz, _vp]
+_lib.acc_linear_bwd_fp8.restype = ctypes.c_int
+_lib.acc_linear_bwd_fp8.argtypes = [_dp, _vp, _vp, ctypes.c_int, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.acc_linear_dw.restype = ctypes.c_int
 _lib.acc_linear_dw.argtypes = [_dp, _vp, _vp, _vp, _vp]
 _lib.acc_linear_bias_grad.restype = ctypes.c_int
@@ -171,6 +177,23 @@ def acc_linear_bwd(desc, dY, W, Xs, dX, Gr, dW, workspace, stream=None, ws_bytes
         ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(_lib.acc_linear_bwd(ctypes.byref(desc), _ptr(dY), _ptr(W), _ptr(Xs), _ptr(dX), _ptr(Gr),
                                _ptr(dW), _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_fwd_fp8(desc, X, X8, W8, scale, Y, Xs, workspace, stream=None, ws_bytes=None):
+    """Enqueue Y = scale * (X8.W8) on 8-bit operands (uint8 tensors of fp8 e4m3 bits) and Xs = X^T.S from the bf16 X."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_linear_fwd_fp8(ctypes.byref(desc), _ptr(X), _ptr(X8), _ptr(W8), float(scale), _ptr(Y), _ptr(Xs),
+                                   _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+def acc_linear_bwd_fp8(desc, dY, dY8, dy8_format, W8, scale, Xs, dX, Gr, dW, workspace, stream=None, ws_bytes=None):
+    """Enqueue dX = scale * (dY8.W8^T) on 8-bit operands, Gr = S^T.dY from the bf16 dY and (dW is not None) dW."""
+    if ws_bytes is None:
+        ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(_lib.acc_linear_bwd_fp8(ctypes.byref(desc), _ptr(dY), _ptr(dY8), int(dy8_format), _ptr(W8), float(scale),
+                                   _ptr(Xs), _ptr(dX), _ptr(Gr), _ptr(dW), _ptr(workspace), ws_bytes,
+                                   _stream(stream)))
 
 
 def acc_linear_dw(desc, Xs, Gr, dW, stream=None):

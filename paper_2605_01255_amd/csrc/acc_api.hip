@@ -19,6 +19,7 @@
 #include "acc_rsvd.h"
 #include "acc_sketch.h"
 #include "acc_gemm16.h"
+#include "acc_gemm8.h"
 #include "acc_gemm_smallk.h"
 
 // Scratch of acc_linear_fwd_static (the entry point for callers that cannot allocate): the split-token partial
@@ -302,6 +303,31 @@ void smallk_gemm(const void* A, const void* B, void* C, int64_t M, int64_t N, in
   p.tiles_m = (int)ceil_div(M, 192);
   p.tiles_n = (int)ceil_div(N, 192);
   L.launch_lds(gemm16_smallk_kernel<KMAJ, TC>, dim3((unsigned)(p.tiles_m * p.tiles_n)), dim3(256), (size_t)144 * 1024, p);
+}
+
+// ---- exact products on 8-bit floating-point operands (acc_gemm8.h) ---------------------------------
+// C[M, N] (bf16) = alpha * (A8[M, K] . B8); B8 is [N, K] (KMAJ) or [K, N]; one byte per element, strides in bytes.
+bool gemm8_ok(int64_t M, int64_t N, int64_t K, int64_t lda, int64_t ldb, bool kmaj) {
+  return K % 128 == 0 && K >= 384 && N % 8 == 0 && lda % 16 == 0 && ldb % 16 == 0 && M * lda <= kMaxOperandBytes &&
+         (kmaj ? N : K) * ldb <= kMaxOperandBytes && 256 * lda <= kMaxOperandBytes && 256 * ldb <= kMaxOperandBytes;
+}
+
+template <bool KMAJ>
+void gemm8(const void* A, int a_format, const void* B, void* C, int64_t M, int64_t N, int64_t K, int64_t lda,
+           int64_t ldb, int64_t ldc, float alpha, Launcher& L, const ReduceJob* job) {
+  FastGemmParams p{};
+  p.alpha = alpha; p.beta = 0.f;
+  p.A = (const bf16*)A; p.B = (const bf16*)B; p.C = C;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+  if (job && job->count) {
+    p.red_part = job->part; p.red_out = job->out; p.red_count = job->count; p.red_G = job->G;
+    p.red_out_bf16 = job->out_bf16;
+    p.red_row = job->row; p.red_ld = job->ld;
+  }
+  const unsigned slots = gemm_bf16_plan(p, 256, 256);
+  p.red_stride = (int64_t)256 * 256 * 4;
+  if (a_format == ACC_FP8_E5M2) L.launch_lds(gemm8_persist_kernel<KMAJ, 1>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)slots);
+  else L.launch_lds(gemm8_persist_kernel<KMAJ, 0>, dim3(256), dim3(256), (size_t)160 * 1024, p, (int)slots);
 }
 
 // K splits of a skinny product: as many as fill the chip's resident work-group slots exactly once (a
@@ -969,6 +995,54 @@ int acc_linear_bwd(const acc_linear_desc* desc, const void* dY, const void* W, c
                backward_gemm_is_tuned(desc, s) ? &job : nullptr);
     exact_backward_gemm(desc, s, dY, W, dX, L, &job);
   }
+  if (dW) dense_dw(desc, s, Xs, Gr, dW, L);
+  return L.status();
+}
+
+int acc_linear_fwd_fp8(const acc_linear_desc* desc, const void* X, const void* X8, const void* W8, float scale,
+                       void* Y, void* Xs, void* workspace, size_t ws_bytes, void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (desc->io_dtype != ACC_BF16) return ACC_ERR_DTYPE;
+  const bool sketch = !(desc->flags & ACC_FLAG_SKIP_SKETCH);
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W8 is [N = d_out, K = d_in]
+  if (!X8 || !W8 || !Y || (sketch && (!X || !Xs)) || !(scale == scale)) return ACC_ERR_INVALID_ARG;
+  if (!gemm8_ok(s.n, s.d_out, s.d_in, s.ldx, s.ldw, w_oi)) return ACC_ERR_SHAPE;
+  if (!aligned16(X) || !aligned16(X8) || !aligned16(W8) || !aligned16(Y) || !aligned16(Xs) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  if (sketch && (!workspace || ws_bytes < workspace_bytes(desc, s, false))) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  ReduceJob job{};  // the sketch (of the bf16 X) leaves its K4 reduction to the GEMM's prologue
+  if (sketch) run_sketch(desc, X, s.ldx, s.d_in, s.n, false, Xs, s.ldf, (float*)workspace, L, &job);
+  if (w_oi) gemm8<true>(X8, ACC_FP8_E4M3, W8, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, scale, L, &job);
+  else gemm8<false>(X8, ACC_FP8_E4M3, W8, Y, s.n, s.d_out, s.d_in, s.ldx, s.ldw, s.ldy, scale, L, &job);
+  return L.status();
+}
+
+int acc_linear_bwd_fp8(const acc_linear_desc* desc, const void* dY, const void* dY8, int dy8_format, const void* W8,
+                       float scale, const void* Xs, void* dX, void* Gr, void* dW, void* workspace, size_t ws_bytes,
+                       void* stream) {
+  Shape s;
+  int rc = validate_desc(desc, &s);
+  if (rc != ACC_OK) return rc;
+  if (desc->io_dtype != ACC_BF16) return ACC_ERR_DTYPE;
+  if (dy8_format != ACC_FP8_E4M3 && dy8_format != ACC_FP8_E5M2) return ACC_ERR_DTYPE;
+  if (desc->flags & ACC_FLAG_SKIP_SKETCH) return ACC_ERR_INVALID_ARG;
+  const bool w_oi = (desc->flags & ACC_FLAG_W_OUT_IN) != 0;  // W8 is [K = d_out, N = d_in]; otherwise [N = d_in, K = d_out]
+  if (!dY || !dY8 || !W8 || !dX || !Gr || (dW && !Xs) || !(scale == scale)) return ACC_ERR_INVALID_ARG;
+  if (!gemm8_ok(s.n, s.d_in, s.d_out, s.ldy, s.ldw, !w_oi)) return ACC_ERR_SHAPE;
+  if (!aligned16(dY) || !aligned16(dY8) || !aligned16(W8) || !aligned16(Xs) || !aligned16(dX) || !aligned16(Gr) ||
+      !aligned16(dW) || !aligned16(workspace))
+    return ACC_ERR_ALIGN;
+  if (!workspace || ws_bytes < workspace_bytes(desc, s, true)) return ACC_ERR_WORKSPACE;
+  if ((rc = check_device()) != ACC_OK) return rc;
+  Launcher L{(hipStream_t)stream};
+  ReduceJob job{};
+  run_sketch(desc, dY, s.ldy, s.d_out, s.n, !w_oi, Gr, s.ldf, (float*)workspace, L, &job);
+  if (w_oi) gemm8<false>(dY8, dy8_format, W8, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, scale, L, &job);
+  else gemm8<true>(dY8, dy8_format, W8, dX, s.n, s.d_in, s.d_out, s.ldy, s.ldw, s.ldx, scale, L, &job);
   if (dW) dense_dw(desc, s, Xs, Gr, dW, L);
   return L.status();
 }

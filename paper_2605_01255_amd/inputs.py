@@ -39,6 +39,54 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+# ----------------------------------------------------------------------------
+# 8-bit floating-point bit helpers (OCP fp8 e4m3 and e5m2; data formatting only)
+# ----------------------------------------------------------------------------
+def _fp8_table(fmt: str) -> np.ndarray:
+    """float32 value of every bit pattern 0x00 .. 0x7F of the format (NaN / inf patterns as nan / inf)."""
+    ebits, mbits, bias = (4, 3, 7) if fmt == "e4m3" else (5, 2, 15)
+    out = np.empty(128, dtype=np.float64)
+    for b in range(128):
+        e, m = b >> mbits, b & ((1 << mbits) - 1)
+        if e == 0:
+            out[b] = m * 2.0 ** (1 - bias - mbits)
+        else:
+            out[b] = (1 + m * 2.0 ** -mbits) * 2.0 ** (e - bias)
+    if fmt == "e4m3":
+        out[0x7F] = np.nan                      # the only NaN; no infinities, largest finite value 448
+    else:
+        out[0x7C] = np.inf
+        out[0x7D:] = np.nan                     # largest finite value 57344
+    return out
+
+
+def fp8_max(fmt: str) -> float:
+    return 448.0 if fmt == "e4m3" else 57344.0
+
+
+def f32_to_fp8_bits(a: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
+    """float32 -> 8-bit float bit patterns (uint8): round to nearest, ties to the even pattern, saturating at the
+    largest finite value (the cast an fp8 training recipe applies after scaling)."""
+    tab = _fp8_table(fmt)
+    last = 0x7E if fmt == "e4m3" else 0x7B      # largest finite pattern
+    pos = tab[:last + 1]
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    mag = np.minimum(np.abs(a).astype(np.float64), pos[-1])
+    hi = np.clip(np.searchsorted(pos, mag, side="left"), 0, last)
+    lo = np.maximum(hi - 1, 0)
+    d_hi, d_lo = pos[hi] - mag, mag - pos[lo]
+    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & ((hi & 1) == 0))
+    bits = np.where(pick_hi, hi, lo).astype(np.uint8)
+    return bits | (np.signbit(a).astype(np.uint8) << np.uint8(7))
+
+
+def fp8_bits_to_f64(bits: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
+    """8-bit float bit patterns (uint8) -> float64 (exact)."""
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    val = _fp8_table(fmt)[bits & np.uint8(0x7F)]
+    return np.where(bits >> np.uint8(7), -val, val)
+
+
 def as_f64(a: np.ndarray) -> np.ndarray:
     """Widen a stored array (float32 values or uint16 bf16 bits) to float64, exactly."""
     if a.dtype == np.uint16:

@@ -1,0 +1,86 @@
+"""The exact products on 8-bit operands (acc_linear_fwd_fp8 / acc_linear_bwd_fp8) against the oracle.
+
+The inputs are the seeded workloads, cast on the host to fp8 with a per-tensor scale (the cast an fp8 training
+recipe applies); the oracle receives the dequantised values in fp64, so what is compared is the arithmetic of the
+layer on exactly those operands: Y = scale (X8 . W8), dX = scale (dY8 . W8^T), bf16 outputs, the spec bar
+plus the per-block and per-element companions.  The sketches are taken from the bf16 tensors as in the bf16 path."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2605_01255_amd import inputs
+from oracle import acc_oracle as orc
+import gpu_util as gu
+
+
+@pytest.fixture(scope="module")
+def acc():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2605_01255_amd import binding
+    return binding
+
+
+def _cast(a_bits, fmt):
+    """bf16 bit patterns -> (fp8 bits, dequantisation scale): the tensor's largest magnitude lands on the format's."""
+    a = inputs.bf16_bits_to_f32(a_bits)
+    amax = float(np.max(np.abs(a)))
+    q = inputs.fp8_max(fmt) / amax if amax > 0 else 1.0
+    q = 2.0 ** np.floor(np.log2(q))                       # power-of-two scale: the cast itself adds no rounding of its own
+    return inputs.f32_to_fp8_bits(a * np.float32(q), fmt), 1.0 / q
+
+
+def _run(acc, lin, data, w_out_in, dy_fmt, want_dw=True):
+    import torch
+    dev = "cuda:0"
+    flags = acc.ACC_FLAG_W_OUT_IN if w_out_in else 0
+    x8, sx = _cast(data["X"], "e4m3")
+    w8, sw = _cast(data["W"], "e4m3")
+    dy8, sdy = _cast(data["dY"], dy_fmt)
+    w_bits = np.ascontiguousarray(w8.T) if w_out_in else w8
+    X, dY = acc.to_device(data["X"], dev), acc.to_device(data["dY"], dev)
+    X8, W8, dY8 = (torch.from_numpy(a).to(dev) for a in (x8, w_bits, dy8))
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed, flags=flags)
+    Y = torch.full((lin.n, lin.d_out), 7.0, dtype=torch.bfloat16, device=dev)
+    dX = torch.full((lin.n, lin.d_in), 7.0, dtype=torch.bfloat16, device=dev)
+    Xs = torch.full((lin.d_in, lin.r), 7.0, dtype=torch.bfloat16, device=dev)
+    Gr = torch.full((lin.d_out, lin.r) if w_out_in else (lin.r, lin.d_out), 7.0, dtype=torch.bfloat16, device=dev)
+    dW = torch.full((lin.d_out, lin.d_in) if w_out_in else (lin.d_in, lin.d_out), 7.0, dtype=torch.bfloat16,
+                    device=dev) if want_dw else None
+    acc.acc_linear_fwd_fp8(desc, X, X8, W8, sx * sw, Y, Xs, acc.alloc_workspace(desc, False, dev))
+    fmt_code = acc.ACC_FP8_E4M3 if dy_fmt == "e4m3" else acc.ACC_FP8_E5M2
+    acc.acc_linear_bwd_fp8(desc, dY, dY8, fmt_code, W8, sdy * sw, Xs, dX, Gr, dW, acc.alloc_workspace(desc, True, dev))
+    torch.cuda.synchronize()
+    got = {"Y": acc.to_host_f64(Y), "Xs": acc.to_host_f64(Xs), "dX": acc.to_host_f64(dX), "Gr": acc.to_host_f64(Gr)}
+    if want_dw:
+        got["dW"] = acc.to_host_f64(dW)
+    # the oracle on the dequantised operands (exact products) and on the bf16 tensors (sketches)
+    Xq = inputs.fp8_bits_to_f64(x8, "e4m3") * sx
+    Wq = inputs.fp8_bits_to_f64(w8, "e4m3") * sw
+    dYq = inputs.fp8_bits_to_f64(dy8, dy_fmt) * sdy
+    S = orc.sketch_matrix(lin.seed, lin.n, lin.r, 0)
+    Wo = np.ascontiguousarray(Wq.T) if w_out_in else Wq
+    Yq, _ = orc.linear_fwd(Xq, Wo, S=S, w_out_in=w_out_in)
+    _, Xs_o = orc.linear_fwd(inputs.as_f64(data["X"]), Wo, S=S, w_out_in=w_out_in)
+    dXq, _, _ = orc.linear_bwd(dYq, Wo, Xs_o, S=S, want_dW=False, w_out_in=w_out_in)
+    _, Gr_o, dW_o = orc.linear_bwd(inputs.as_f64(data["dY"]), Wo, Xs_o, S=S, want_dW=want_dw, w_out_in=w_out_in)
+    want = {"Y": Yq, "Xs": Xs_o, "dX": dXq, "Gr": Gr_o}
+    if want_dw:
+        want["dW"] = dW_o
+    return got, want
+
+
+@pytest.mark.parametrize("w_out_in", [False, True])
+@pytest.mark.parametrize("n,d_in,d_out,r,dy_fmt", [
+    (700, 512, 640, 64, "e4m3"),      # 3 x 3 and 3 x 2 tiles with ragged last rows, four and five K tiles
+    (1000, 384, 1152, 32, "e5m2"),    # the shortest contraction the path takes (three K tiles), half a tile of columns
+    (256, 1024, 384, 64, "e5m2"),     # one row of tiles
+])
+def test_fp8_exact_products_small(acc, n, d_in, d_out, r, dy_fmt, w_out_in):
+    lin = inputs.Linear(f"fp8_{n}_{d_in}_{d_out}", n, d_in, d_out, r, seed=11)
+    data = inputs.make(lin)
+    print(f"fp8 case n={n} {d_in}->{d_out} r={r} dY8={dy_fmt} w_out_in={w_out_in}", flush=True)
+    got, want = _run(acc, lin, data, w_out_in, dy_fmt)
+    gu.check_outputs(got, want, 1e-2, lin.name)
