@@ -57,13 +57,14 @@ __device__ __forceinline__ void buffer_to_lds_b128_sum(u32x4 rsrc, uint32_t voff
 template <bool B_KMAJOR, int A_FMT>
 __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, int n_slots) {
   constexpr int BAR_Q = 32;  // the barrier sits before this slot
+  constexpr int DMA_EVERY = 2;  // one wave-load every second slot after the barrier
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int NW = 4, WN = 2, TB = 8;
   constexpr int BM = 256, BN = 256, BK = 128;
   constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
   constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW, NG = A_LOADS + B_LOADS;
   constexpr int REGION = 16 * 256;  // one staged block row: 16 rows x 128 bf16
-  static_assert(NG == 16 && BAR_Q + 1 + 2 * (NG - 1) < 64, "the slot program places sixteen wave-loads per K tile");
+  static_assert(NG == 16 && BAR_Q + 1 + DMA_EVERY * (NG - 1) < 64, "the slot program places sixteen wave-loads per K tile");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -175,8 +176,8 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
-  __amdgpu_buffer_rsrc_t c_rs;
-  uint32_t c_voff;
+  __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc((void*)C, 0, 0, 0x00020000);  // empty: nothing to store yet
+  uint32_t c_voff = 0xFFFFFFF0u;
   auto set_output = [&](const TileRef& t) {
     const int64_t gm_base = t.m0 + wm * TB * 16, gn_base = t.n0 + wn * TB * 16;
     int64_t c_rows = p.M - gm_base;
@@ -199,18 +200,18 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
   };
   auto store_back = [&](int i, int t, u32x4 v) {
     const uint32_t soff = (uint32_t)(i * 16 + t * 4) * c_row_bytes;
-    __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff, soff, 0);
+    __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff, soff, 2);  // aux 2: non-temporal (see the header)
   };
-  u32x4 back[4];
-  // what is left of the previous output tile's read-out (block rows 6 and 7), as work for slots 0 .. 7
-  auto carry_slot = [&](int q) {
+  u32x4 back[2];
+  // What is left of the previous output tile's read-out: block rows 6 and 7 sit in the two staging regions when
+  // its last K tile ends (row 7 is staged after that tile's last matrix instruction, so no accumulator lives on
+  // into the next output tile); their read-backs and global stores ride in slots 33 .. 40 of the next K tile,
+  // behind its barrier, so that the barrier's wait for the transfers does not also wait for stores just issued.
+  auto carry_store = [&](int q) {  // q = 0 .. 7
     if (q == 0) wave_fence();
-    if (q < 4) { stage_write(7, 2 * q); stage_write(7, 2 * q + 1); }
-    if (q < 2) { back[2 * q] = read_back(6, 2 * q); back[2 * q + 1] = read_back(6, 2 * q + 1); }
-    else if (q < 4) { store_back(6, 2 * q - 4, back[2 * q - 4]); store_back(6, 2 * q - 3, back[2 * q - 3]); }
-    if (q == 4) wave_fence();
-    if (q >= 4 && q < 6) { back[2 * q - 8] = read_back(7, 2 * q - 8); back[2 * q - 7] = read_back(7, 2 * q - 7); }
-    if (q >= 6 && q < 8) { store_back(7, 2 * q - 12, back[2 * q - 12]); store_back(7, 2 * q - 11, back[2 * q - 11]); }
+    const int row = 6 + (q >> 2), t = q & 2;
+    if ((q & 1) == 0) { back[0] = read_back(row, t); back[1] = read_back(row, t + 1); }
+    else { store_back(row, t, back[0]); store_back(row, t + 1, back[1]); }
   };
 
   i32x8 a[TB], b[TB];
@@ -240,22 +241,26 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
       if (h == 0) {
         // B operands 4 .. 7 of this K tile (slots 2, 8, 14, 20)
         if (q >= 2 && (q - 2) % 6 == 0 && (q - 2) / 6 < 4) b[4 + (q - 2) / 6] = read_b(cur, 4 + (q - 2) / 6);
-        if (CARRY && q < 8) carry_slot(q);
       } else {
         // operands of the next K tile: A operand i once block row i is done, B operands 0 .. 3 at slots 34, 42, 50, 58
         if (jj == 0 && i >= 1) a[i - 1] = read_a(nxt, i - 1);
         if (q >= BAR_Q + 2 && (q - BAR_Q - 2) % 8 == 0) b[(q - BAR_Q - 2) / 8] = read_b(nxt, (q - BAR_Q - 2) / 8);
-        if (q >= BAR_Q + 1 && (q - BAR_Q - 1) % 2 == 0 && (q - BAR_Q - 1) / 2 < NG)
-          issue_one(ref2, (q - BAR_Q - 1) / 2, k2, cur_lds);
+        if (q >= BAR_Q + 1 && (q - BAR_Q - 1) % DMA_EVERY == 0 && (q - BAR_Q - 1) / DMA_EVERY < NG)
+          issue_one(ref2, (q - BAR_Q - 1) / DMA_EVERY, k2, cur_lds);
+        if (CARRY && q >= BAR_Q + 1 && q < BAR_Q + 9) carry_store(q - BAR_Q - 1);
         if constexpr (FINAL) {
           // block row i - 1 is final: staged in the slots of row i; read back and stored in those of row i + 1
           if (i >= 2 && jj == 0) wave_fence();
           if (i >= 1) { stage_write(i - 1, 2 * jj); stage_write(i - 1, 2 * jj + 1); }
-          if (i >= 2 && jj < 2) { back[2 * jj] = read_back(i - 2, 2 * jj); back[2 * jj + 1] = read_back(i - 2, 2 * jj + 1); }
-          if (i >= 2 && jj >= 2) { store_back(i - 2, 2 * jj - 4, back[2 * jj - 4]); store_back(i - 2, 2 * jj - 3, back[2 * jj - 3]); }
+          if (i >= 2 && (jj & 1) == 0) { back[0] = read_back(i - 2, jj); back[1] = read_back(i - 2, jj + 1); }
+          if (i >= 2 && (jj & 1) == 1) { store_back(i - 2, jj - 1, back[0]); store_back(i - 2, jj, back[1]); }
         }
       }
       __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (FINAL) {
+#pragma unroll
+      for (int j = 0; j < TB; ++j) stage_write(TB - 1, j);
     }
   };
 
@@ -297,13 +302,15 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     const int next_idx = next_slot(idx);
     const bool has_next = next_idx < n_slots;
     const TileRef next_t = has_next ? tile_ref(next_idx) : cur_t;
-    // K tile 0: multiplies onto zero and, after the first output tile, finishes the previous read-out
-    if (idx == first_idx) ktile(par, cur_t, 2, T{}, F{}, F{});
-    else ktile(par, cur_t, 2, T{}, T{}, F{});
-    int kt = 1;
-    for (; kt + 2 < KT; ++kt) ktile((kt + par) & 1, cur_t, kt + 2, F{}, F{}, F{});
-    ktile((kt + par) & 1, next_t, 0, F{}, F{}, F{});  // last but one
-    ++kt;
+    // K tile 0: multiplies onto zero and finishes the previous read-out (before the first output tile the
+    // accumulators hold nothing and the output resource is empty, so those stores are dropped)
+    ktile(par, cur_t, 2, T{}, T{}, F{});
+    // K tiles 1 .. KT - 2; the last of them already fetches the next output tile's first K tile
+    for (int kt = 1; kt + 1 < KT; ++kt) {
+      const bool wraps = kt + 2 >= KT;
+      ktile((kt + par) & 1, wraps ? next_t : cur_t, wraps ? 0 : kt + 2, F{}, F{}, F{});
+    }
+    const int kt = KT - 1;
     set_output(cur_t);
     ktile((kt + par) & 1, next_t, 1, F{}, F{}, T{});  // last: the read-out starts
     if (!has_next) break;
@@ -313,7 +320,7 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
   }
   // no tile follows: block rows 6 and 7 are read out here
 #pragma unroll
-  for (int q = 0; q < 8; ++q) carry_slot(q);
+  for (int q = 0; q < 8; ++q) carry_store(q);
   wait_vmcnt0();  // the surplus transfers of the last two K tiles must have landed before the LDS is released
 }
 
