@@ -53,18 +53,33 @@ __device__ __forceinline__ void buffer_to_lds_b128_sum(u32x4 rsrc, uint32_t voff
                : "memory");
 }
 
+// Compile-time loop: f(integral_constant<int, B>) ... f(integral_constant<int, E - 1>).  The slot program indexes
+// its register arrays with the slot number; with an ordinary loop the compiler has to unroll it before it can
+// keep those arrays in registers, and when it does that too late they end up in scratch memory (same results,
+// thirty times slower).
+template <int B, int E, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 // A_FMT: 0 = fp8 (e4m3), 1 = bf8 (e5m2) for the A operand; B is always fp8 (e4m3).
 template <bool B_KMAJOR, int A_FMT>
 __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, int n_slots) {
-  constexpr int BAR_Q = 32;  // the barrier sits before this slot
-  constexpr int DMA_EVERY = 2;  // one wave-load every second slot after the barrier
+  // One barrier per K tile, before slot BAR_Q: every wave has read its last operands of this K tile's stage (it can
+  // be refilled) and the next K tile's stage has landed.  The sixteen wave-loads of the K tile after next follow in
+  // the odd slots DMA_Q, DMA_Q + 2, ...; the operand reads sit in even slots.  Measured against it on the 3B-shaped
+  // projection: a barrier of its own for the release (before slot 21, transfers from slot 23, the landing barrier
+  // waiting for all but the five youngest) 135.1 against 124.9 us; one wave-load per slot 146.6 against 140.1 us.
+  constexpr int BAR_Q = 32, DMA_Q = 33, DMA_EVERY = 2;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int NW = 4, WN = 2, TB = 8;
   constexpr int BM = 256, BN = 256, BK = 128;
   constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
   constexpr int A_LOADS = A_BYTES / 1024 / NW, B_LOADS = B_BYTES / 1024 / NW, NG = A_LOADS + B_LOADS;
   constexpr int REGION = 16 * 256;  // one staged block row: 16 rows x 128 bf16
-  static_assert(NG == 16 && BAR_Q + 1 + DMA_EVERY * (NG - 1) < 64, "the slot program places sixteen wave-loads per K tile");
+  static_assert(NG == 16 && DMA_Q + DMA_EVERY * (NG - 1) < 64 && DMA_Q > BAR_Q && BAR_Q > 20 && BAR_Q < 34, "the slot program places sixteen wave-loads per K tile");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -223,9 +238,9 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     const char* nxt = smem + (sc ^ 1) * STAGE;
     const uint32_t cur_lds = smem_lds + sc * STAGE;
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int q = 0; q < 64; ++q) {
-      const int h = q >> 5, i = (q >> 2) & 7, jj = q & 3, j = 4 * h + jj;
+    static_for<0, 64>([&](auto slot) {
+      constexpr int q = decltype(slot)::value;
+      constexpr int h = q >> 5, i = (q >> 2) & 7, jj = q & 3, j = 4 * h + jj;
       if (q == 0) a[7] = read_a(cur, 7);
       if (q == BAR_Q) {
         wait_vmcnt0();
@@ -238,6 +253,8 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
       } else {
         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], 0, A_FMT, 0, 0, 0, 0);
       }
+      if (q >= DMA_Q && (q - DMA_Q) % DMA_EVERY == 0 && (q - DMA_Q) / DMA_EVERY < NG)
+        issue_one(ref2, (q - DMA_Q) / DMA_EVERY, k2, cur_lds);
       if (h == 0) {
         // B operands 4 .. 7 of this K tile (slots 2, 8, 14, 20)
         if (q >= 2 && (q - 2) % 6 == 0 && (q - 2) / 6 < 4) b[4 + (q - 2) / 6] = read_b(cur, 4 + (q - 2) / 6);
@@ -245,8 +262,6 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
         // operands of the next K tile: A operand i once block row i is done, B operands 0 .. 3 at slots 34, 42, 50, 58
         if (jj == 0 && i >= 1) a[i - 1] = read_a(nxt, i - 1);
         if (q >= BAR_Q + 2 && (q - BAR_Q - 2) % 8 == 0) b[(q - BAR_Q - 2) / 8] = read_b(nxt, (q - BAR_Q - 2) / 8);
-        if (q >= BAR_Q + 1 && (q - BAR_Q - 1) % DMA_EVERY == 0 && (q - BAR_Q - 1) / DMA_EVERY < NG)
-          issue_one(ref2, (q - BAR_Q - 1) / DMA_EVERY, k2, cur_lds);
         if (CARRY && q >= BAR_Q + 1 && q < BAR_Q + 9) carry_store(q - BAR_Q - 1);
         if constexpr (FINAL) {
           // block row i - 1 is final: staged in the slots of row i; read back and stored in those of row i + 1
@@ -257,10 +272,9 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
         }
       }
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
     if constexpr (FINAL) {
-#pragma unroll
-      for (int j = 0; j < TB; ++j) stage_write(TB - 1, j);
+      static_for<0, TB>([&](auto j) { stage_write(TB - 1, decltype(j)::value); });
     }
   };
 
