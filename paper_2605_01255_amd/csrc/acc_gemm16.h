@@ -27,15 +27,19 @@
 // Measured on the 3B-shaped projection (a step of the layer, same-box pairs): barrier before slot 72 0.547 - 0.552
 // ms against 0.553 - 0.557 before slot 80; before slot 88 0.545 - 0.546 against 0.541 - 0.542 before slot 80; all
 // sixteen wave-loads after the barrier, one every three slots, 0.565 against 0.553 - 0.557; eight after it and
-// eight in the next k-step 0: equal; one wave-load every second slot: thirty times slower (the transfers queue up
-// behind each other), never do that.  Spreading the wave-loads evenly (nine after the barrier, one every six
+// eight in the next k-step 0: equal; one wave-load every second slot: 0.561 against 0.550.  Spreading the wave-loads evenly (nine after the barrier, one every six
 // slots, seven in the next k-step 0, one every six) 0.5545 against 0.5507; the last of them 14 slots before the
 // barrier instead of 58: 0.584 (the transfers need their thousand clocks to land).
 // What is left inside a K tile (in-kernel timestamps): 2924 clocks, of which the wait for the transfers is 8 and the
 // barrier 67; the matrix instructions alone need 2048 back to back, about 2380 at the rate one wave issues them, and
 // the rest is the issue of the sixteen 1 KB transfers per wave (a wave issues in order).  Two waves per SIMD (eight
-// waves of 128 x 64) hide that but read 1.5 x the operand bytes from LDS: equal in time.  Four consecutive wave-loads
-// sharing one LDS base in M0 through the instruction's immediate offset: correct, thirty times slower.
+// waves of 128 x 64) hide that but read 1.5 x the operand bytes from LDS: equal in time.
+// A warning about builds, not about the hardware: the slot loops index the register arrays (acc, a, b0, b1) with the
+// slot number, so the arrays stay in registers only if the compiler unrolls those loops before it decides where
+// arrays live.  Two earlier variants of this kernel (denser wave-loads; four wave-loads sharing one LDS base in M0
+// through the instruction's immediate offset) came out with the arrays in scratch memory: same results, thirty
+// times slower.  After any change check that the kernel's scratch size is still zero
+// (-Rpass-analysis=kernel-resource-usage); acc_gemm8.h avoids the question with a compile-time loop.
 #pragma once
 #include <type_traits>
 
