@@ -71,13 +71,19 @@ def f32_to_fp8_bits(a: np.ndarray, fmt: str = "e4m3") -> np.ndarray:
     last = 0x7E if fmt == "e4m3" else 0x7B      # largest finite pattern
     pos = tab[:last + 1]
     a = np.ascontiguousarray(a, dtype=np.float32)
-    mag = np.minimum(np.abs(a).astype(np.float64), pos[-1])
-    hi = np.clip(np.searchsorted(pos, mag, side="left"), 0, last)
-    lo = np.maximum(hi - 1, 0)
-    d_hi, d_lo = pos[hi] - mag, mag - pos[lo]
-    pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & ((hi & 1) == 0))
-    bits = np.where(pick_hi, hi, lo).astype(np.uint8)
-    return bits | (np.signbit(a).astype(np.uint8) << np.uint8(7))
+    flat = a.reshape(-1)
+    out = np.empty(flat.shape, dtype=np.uint8)
+    step = 1 << 22                              # bounded temporaries for operands of a gigabyte
+    for s0 in range(0, flat.size, step):
+        v = flat[s0:s0 + step]
+        mag = np.minimum(np.abs(v).astype(np.float64), pos[-1])
+        hi = np.clip(np.searchsorted(pos, mag, side="left"), 0, last)
+        lo = np.maximum(hi - 1, 0)
+        d_hi, d_lo = pos[hi] - mag, mag - pos[lo]
+        pick_hi = (d_hi < d_lo) | ((d_hi == d_lo) & ((hi & 1) == 0))
+        bits = np.where(pick_hi, hi, lo).astype(np.uint8)
+        out[s0:s0 + step] = bits | (np.signbit(v).astype(np.uint8) << np.uint8(7))
+    return out.reshape(a.shape)
 
 
 def fp8_bits_to_f64(bits: np.ndarray, fmt: str = "e4m3") -> np.ndarray:

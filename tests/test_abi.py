@@ -277,3 +277,38 @@ def test_mfma_probe_hook_validates_arguments():
     assert f(0, 1, 0, 0, 0x1000, big, ctypes.byref(fl), None) == -2
     assert f(0, 1, 0, 100, 0x1004, big, ctypes.byref(fl), None) == -3
     assert f(1, 2, 1, 100, 0x1000, 256 * 512 * 4 - 1, ctypes.byref(fl), None) == -5
+
+
+def test_fp8_entry_points_validate_before_they_touch_a_device():
+    fwd, bwd = acc._lib.acc_linear_fwd_fp8, acc._lib.acc_linear_bwd_fp8
+    ws = 1 << 26
+    ok = acc.make_desc(1000, 512, 640, 64)
+
+    def f(d, X=0x1000, X8=0x2000, W8=0x3000, scale=1.0, Y=0x4000, Xs=0x5000, w=0x6000):
+        return fwd(ctypes.byref(d), X, X8, W8, ctypes.c_float(scale), Y, Xs, w, ws, None)
+
+    def b(d, dY=0x1000, dY8=0x2000, fmt=acc.ACC_FP8_E5M2, W8=0x3000, scale=1.0, Xs=0x4000, dX=0x5000, Gr=0x6000,
+          dW=0x7000, w=0x8000):
+        return bwd(ctypes.byref(d), dY, dY8, fmt, W8, ctypes.c_float(scale), Xs, dX, Gr, dW, w, ws, None)
+
+    assert f(ok) in (0, -6) and b(ok) in (0, -6)
+    assert fwd(None, 0x1000, 0x2000, 0x3000, ctypes.c_float(1.0), 0x4000, 0x5000, 0x6000, ws, None) == -1
+    assert f(ok, X8=0) == -1 and f(ok, W8=0) == -1 and f(ok, Y=0) == -1 and f(ok, X=0) == -1 and f(ok, Xs=0) == -1
+    assert f(ok, scale=float("nan")) == -1 and b(ok, scale=float("nan")) == -1
+    assert f(ok, X8=0x2004) == -3 and b(ok, dY8=0x2008) == -3
+    assert b(ok, dY8=0) == -1 and b(ok, fmt=2) == -4 and b(ok, Xs=0) == -1 and b(ok, Xs=0, dW=0) in (0, -6)
+    # fp32 tensors beside the 8-bit operands are not supported
+    assert f(acc.make_desc(1000, 512, 640, 64, io_dtype=acc.ACC_F32)) == -4
+    # with the sketch skipped neither X nor Xs nor a workspace is needed
+    skip = acc.make_desc(1000, 512, 640, 64, flags=acc.ACC_FLAG_SKIP_SKETCH)
+    assert fwd(ctypes.byref(skip), None, 0x2000, 0x3000, ctypes.c_float(1.0), 0x4000, None, None, 0, None) in (0, -6)
+    assert b(skip) == -1
+    # contraction length: a multiple of 128, at least 384 (d_in forward, d_out backward); no slower fall-back
+    assert f(acc.make_desc(1000, 448, 640, 64)) == -2 and f(acc.make_desc(1000, 256, 640, 64)) == -2
+    assert b(acc.make_desc(1000, 512, 576, 64)) == -2 and b(acc.make_desc(1000, 512, 256, 64)) == -2
+    assert f(acc.make_desc(1000, 512, 576, 64)) in (0, -6)     # forward only needs d_out % 16 (a 16-byte row of W8)
+    assert f(acc.make_desc(1000, 512, 648, 64)) == -2
+    # row strides of the 8-bit operands: multiples of 16 bytes
+    assert f(acc.make_desc(1000, 512, 640, 64, ldx=520)) == -2 and f(acc.make_desc(1000, 512, 640, 64, ldx=528)) in (0, -6)
+    # too small a workspace
+    assert fwd(ctypes.byref(ok), 0x1000, 0x2000, 0x3000, ctypes.c_float(1.0), 0x4000, 0x5000, 0x6000, 16, None) == -5

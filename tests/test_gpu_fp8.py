@@ -26,13 +26,15 @@ def acc():
 def _cast(a_bits, fmt):
     """bf16 bit patterns -> (fp8 bits, dequantisation scale): the tensor's largest magnitude lands on the format's."""
     a = inputs.bf16_bits_to_f32(a_bits)
-    amax = float(np.max(np.abs(a)))
+    amax = float(max(np.max(a), -np.min(a)))
     q = inputs.fp8_max(fmt) / amax if amax > 0 else 1.0
     q = 2.0 ** np.floor(np.log2(q))                       # power-of-two scale: the cast itself adds no rounding of its own
-    return inputs.f32_to_fp8_bits(a * np.float32(q), fmt), 1.0 / q
+    a *= np.float32(q)
+    return inputs.f32_to_fp8_bits(a, fmt), 1.0 / q
 
 
-def _run(acc, lin, data, w_out_in, dy_fmt, want_dw=True):
+def _device_pass(acc, lin, data, w_out_in, dy_fmt, want_dw=True):
+    """Forward + backward through the fp8 entry points.  Returns (outputs as float64, the 8-bit casts and scales)."""
     import torch
     dev = "cuda:0"
     flags = acc.ACC_FLAG_W_OUT_IN if w_out_in else 0
@@ -56,10 +58,15 @@ def _run(acc, lin, data, w_out_in, dy_fmt, want_dw=True):
     got = {"Y": acc.to_host_f64(Y), "Xs": acc.to_host_f64(Xs), "dX": acc.to_host_f64(dX), "Gr": acc.to_host_f64(Gr)}
     if want_dw:
         got["dW"] = acc.to_host_f64(dW)
+    return got, {"x8": x8, "w8": w8, "dy8": dy8, "sx": sx, "sw": sw, "sdy": sdy}
+
+
+def _run(acc, lin, data, w_out_in, dy_fmt, want_dw=True):
+    got, q = _device_pass(acc, lin, data, w_out_in, dy_fmt, want_dw)
     # the oracle on the dequantised operands (exact products) and on the bf16 tensors (sketches)
-    Xq = inputs.fp8_bits_to_f64(x8, "e4m3") * sx
-    Wq = inputs.fp8_bits_to_f64(w8, "e4m3") * sw
-    dYq = inputs.fp8_bits_to_f64(dy8, dy_fmt) * sdy
+    Xq = inputs.fp8_bits_to_f64(q["x8"], "e4m3") * q["sx"]
+    Wq = inputs.fp8_bits_to_f64(q["w8"], "e4m3") * q["sw"]
+    dYq = inputs.fp8_bits_to_f64(q["dy8"], dy_fmt) * q["sdy"]
     S = orc.sketch_matrix(lin.seed, lin.n, lin.r, 0)
     Wo = np.ascontiguousarray(Wq.T) if w_out_in else Wq
     Yq, _ = orc.linear_fwd(Xq, Wo, S=S, w_out_in=w_out_in)
@@ -84,3 +91,59 @@ def test_fp8_exact_products_small(acc, n, d_in, d_out, r, dy_fmt, w_out_in):
     print(f"fp8 case n={n} {d_in}->{d_out} r={r} dY8={dy_fmt} w_out_in={w_out_in}", flush=True)
     got, want = _run(acc, lin, data, w_out_in, dy_fmt)
     gu.check_outputs(got, want, 1e-2, lin.name)
+
+
+def test_fp8_c2_every_element(acc):
+    """The benchmark's projection (n = 16384, 3072 -> 3072, r = 256) in the launch configuration bench.py times:
+    every element of every output."""
+    lin = inputs.config("c2")[0]
+    data = inputs.make(lin)
+    print("fp8 c2 whole outputs", flush=True)
+    got, want = _run(acc, lin, data, False, "e5m2")
+    gu.check_outputs(got, want, 1e-2, lin.name + ".fp8")
+
+
+def test_fp8_factors_equal_the_bf16_path_bit_for_bit(acc):
+    """The sketches do not depend on the 8-bit operands: Xs, Gr and dW of the fp8 calls are the bits the bf16
+    calls produce on the same X and dY."""
+    lin = inputs.Linear("fp8_same_factors", 2048, 1024, 768, 64, seed=5)
+    data = inputs.make(lin)
+    got8, _ = _device_pass(acc, lin, data, False, "e4m3")
+    got16 = gu.run_layer(acc, lin, data)
+    for k in ("Xs", "Gr", "dW"):
+        assert np.array_equal(got8[k], got16[k]), k
+
+
+@pytest.mark.parametrize("cfg,name", [("c4", "c4.gate"), ("c5", "c5.down")])
+def test_fp8_large_linears_sampled(acc, cfg, name):
+    """3072 -> 8192 (32 x 64 output tiles) and the 8B-shaped down projection (n = 65536, 14336 -> 4096: 112 K tiles
+    per output tile, a 0.94 GB 8-bit input): 256 random token rows of Y and dX and three whole 256 x 256 output
+    tiles of each (first, a random one, last) against the oracle on the dequantised operands."""
+    lin = [l for l in inputs.config(cfg) if l.name == name][0]
+    rng = np.random.default_rng(8)
+    data = inputs.make(lin)
+    print(f"fp8 sampled {name}", flush=True)
+    got, q = _device_pass(acc, lin, data, False, "e5m2", want_dw=False)
+    sx, sw, sdy = q["sx"], q["sw"], q["sdy"]
+    Wq = inputs.fp8_bits_to_f64(q["w8"], "e4m3") * sw
+    rows = np.sort(rng.choice(lin.n, size=256, replace=False))
+    have = {"Y": got["Y"][rows], "dX": got["dX"][rows]}
+    want = {"Y": orc.linear_fwd(inputs.fp8_bits_to_f64(q["x8"][rows], "e4m3") * sx, Wq, S=np.zeros((256, lin.r)))[0],
+            "dX": orc.linear_bwd(inputs.fp8_bits_to_f64(q["dy8"][rows], "e5m2") * sdy, Wq, np.zeros((lin.d_in, lin.r)),
+                                 S=np.zeros((256, lin.r)), want_dW=False)[0]}
+
+    def tiles(extent_m, extent_n):
+        tm, tn = -(-extent_m // 256), -(-extent_n // 256)
+        picks = {(0, 0), (int(rng.integers(tm)), int(rng.integers(tn))), (tm - 1, tn - 1)}
+        return [(slice(a * 256, min(extent_m, a * 256 + 256)), slice(b * 256, min(extent_n, b * 256 + 256)))
+                for a, b in sorted(picks)]
+    for i, (rs, cs) in enumerate(tiles(lin.n, lin.d_out)):
+        have[f"Y.tile{i}"] = got["Y"][rs, cs]
+        want[f"Y.tile{i}"] = orc.linear_fwd(inputs.fp8_bits_to_f64(q["x8"][rs], "e4m3") * sx, Wq[:, cs],
+                                            S=np.zeros((rs.stop - rs.start, lin.r)))[0]
+    for i, (rs, cs) in enumerate(tiles(lin.n, lin.d_in)):
+        have[f"dX.tile{i}"] = got["dX"][rs, cs]
+        want[f"dX.tile{i}"] = orc.linear_bwd(inputs.fp8_bits_to_f64(q["dy8"][rs], "e5m2") * sdy, Wq[cs],
+                                             np.zeros((cs.stop - cs.start, lin.r)),
+                                             S=np.zeros((rs.stop - rs.start, lin.r)), want_dW=False)[0]
+    gu.check_outputs(have, want, 1e-2, name + ".fp8")
