@@ -12,8 +12,8 @@
 // output tiles, K pipeline across output tiles, two 64 KB LDS stages filled global -> LDS directly, read-out of a
 // finished block row under the matrix instructions that follow.  A K tile is 128 elements = 128 bytes per row, so
 // the transfers, the LDS layout and the swizzle of a K-contiguous tile are those of the bf16 kernel; what differs:
-//   * one instruction covers the whole K tile of a 16 x 16 block (each lane holds 32 consecutive k of its row:
-//     two 16-byte LDS reads), so a K tile is 64 slots of one matrix instruction (8 passes, 32 clocks) each;
+//   * one instruction covers the whole K tile of a 16 x 16 block (each lane holds 32 k of its row: two 16-byte
+//     LDS reads), so a K tile is 64 slots of one matrix instruction (8 passes, 32 clocks) each;
 //   * both operand sets are single-buffered (128 registers): the 64 instructions run as two halves, block
 //     columns 0..3 for all eight block rows, then block columns 4..7.  B operands 4..7 of a K tile are read
 //     during its first half, B operands 0..3 of the next K tile during its second half (after the barrier),
@@ -31,9 +31,9 @@
 namespace acc {
 
 // Swizzle of an N-contiguous 8-bit B tile (rows of 256 bytes, one k each): 16-byte chunk c of row k is stored at
-// chunk position c ^ swz_n8(k).  One transposing read touches rows 32 g + 8 c + (0..7) for the four lane groups g:
-// the 8 rows and the parity of g select 16 different chunk positions.
-__device__ __forceinline__ int swz_n8(int krow) { return (krow & 7) | (((krow >> 5) & 1) << 3); }
+// chunk position c ^ swz_n8(k).  One transposing read touches rows 16 g + (0..7) (+ 8, + 64 or + 72) for the four
+// lane groups g: the 8 rows and the parity of g select 16 different chunk positions.
+__device__ __forceinline__ int swz_n8(int krow) { return (krow & 7) | (((krow >> 4) & 1) << 3); }
 
 __device__ __forceinline__ u32x2 lds_read_tr8_b64(const char* lds, int byte_off) {
   typedef int v2i __attribute__((ext_vector_type(2)));
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
   // ---- global -> LDS sources (relative to a tile's buffer resources) ----
   // Wave-load t of a wave covers rows (4 t + wave) * 8 + lane / 8 of a K-contiguous tile: the part that depends on
   // t (and on the K tile) is the same for all lanes, so one register holds the lane's part for all of them.  In an
-  // N-contiguous B tile a wave-load is four k-rows of 256 bytes and the swizzle of a row depends on bit 1 of t.
+  // N-contiguous B tile a wave-load is four k-rows of 256 bytes and the swizzle of a row depends on bit 0 of t.
   const int row0 = wave * 8 + (lane >> 3);
   const uint32_t a_voff = (uint32_t)(row0 * p.lda + (((lane & 7) ^ swz(row0)) << 4));
   uint32_t b_voff[2];
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
   } else {
     const int krow0 = wave * 4 + (lane >> 4);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) b_voff[u] = (uint32_t)(krow0 * p.ldb + (((lane & 15) ^ swz_n8(krow0 + 32 * u)) << 4));
+    for (int u = 0; u < 2; ++u) b_voff[u] = (uint32_t)(krow0 * p.ldb + (((lane & 15) ^ swz_n8(krow0 + 16 * u)) << 4));
   }
   const uint32_t a_tstep = (uint32_t)(32 * p.lda), b_tstep = (uint32_t)((B_KMAJOR ? 32 : 16) * p.ldb);
   const uint32_t b_kstep = B_KMAJOR ? BK : (uint32_t)(BK * p.ldb);
@@ -126,16 +126,21 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     if (g < A_LOADS)
       buffer_to_lds_b128_sum(r.a_rsrc, a_voff, (uint32_t)kt * BK + g * a_tstep, stage + (g * NW + wave) * 1024);
     else
-      buffer_to_lds_b128_sum(r.b_rsrc, b_voff[((g - A_LOADS) >> 1) & 1], (uint32_t)kt * b_kstep + (g - A_LOADS) * b_tstep,
+      buffer_to_lds_b128_sum(r.b_rsrc, b_voff[(g - A_LOADS) & 1], (uint32_t)kt * b_kstep + (g - A_LOADS) * b_tstep,
                              stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024);
   };
 
-  // ---- LDS read offsets of the operands: lane (l16, g4) holds k = 32 g4 .. 32 g4 + 31 of row / column l16 ----
+  // ---- LDS read offsets of the operands ----
+  // Lane (l16, g4) holds, for row / column l16, k = 16 g4 .. 16 g4 + 15 (16-byte chunk g4 of the row) in its first
+  // four registers and k = 64 + 16 g4 .. (chunk 4 + g4) in the other four.  Which k a lane holds is free as long as
+  // both operands agree (the instruction pairs register bytes, not k values); with this choice the four lane groups
+  // of one 16-byte read take four neighbouring chunks, the pattern of the bf16 kernel, which its swizzle serves
+  // without bank conflicts (chunks 2 g4 and 2 g4 + 1 per lane: conflicts in 49 % of the LDS-active cycles).
   const int rswz = swz(l16);
   const int a_row = (wm * TB * 16 + l16) * 128;
   int kc[2];
 #pragma unroll
-  for (int c = 0; c < 2; ++c) kc[c] = ((2 * g4 + c) ^ rswz) << 4;
+  for (int c = 0; c < 2; ++c) kc[c] = ((4 * c + g4) ^ rswz) << 4;
   auto two_chunks = [&](const char* st, int row_off) -> i32x8 {
     const u32x4 lo = *(const u32x4*)(st + row_off + kc[0]);
     const u32x4 hi = *(const u32x4*)(st + row_off + kc[1]);
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
       b_rd[j] = A_BYTES + (wn * TB * 16 + j * 16 + l16) * 128;
     } else {
       const int n_off = (wn * TB + j) * 16 + 8 * (l16 & 1);
-      const int krow = 32 * g4 + (l16 >> 1);
+      const int krow = 16 * g4 + (l16 >> 1);
       b_rd[j] = A_BYTES + krow * BN + (((n_off >> 4) ^ swz_n8(krow)) << 4) + (n_off & 15);
     }
   }
@@ -157,11 +162,11 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     if (B_KMAJOR) {
       return two_chunks(st, b_rd[j]);
     } else {
-      // k rows 8 c + (0..7) of the lane group's 32: the swizzle of a row does not depend on c
+      // k rows 16 g4 + (0..7), + 8, + 64, + 72: the swizzle of a row is the same for the four
       const u32x2 r0 = lds_read_tr8_b64(st, b_rd[j]);
       const u32x2 r1 = lds_read_tr8_b64(st, b_rd[j] + 8 * BN);
-      const u32x2 r2 = lds_read_tr8_b64(st, b_rd[j] + 16 * BN);
-      const u32x2 r3 = lds_read_tr8_b64(st, b_rd[j] + 24 * BN);
+      const u32x2 r2 = lds_read_tr8_b64(st, b_rd[j] + 64 * BN);
+      const u32x2 r3 = lds_read_tr8_b64(st, b_rd[j] + 72 * BN);
       const u32x4 lo = __builtin_shufflevector(r0, r1, 0, 1, 2, 3);
       const u32x4 hi = __builtin_shufflevector(r2, r3, 0, 1, 2, 3);
       return __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
