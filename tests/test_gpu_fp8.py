@@ -147,3 +147,50 @@ def test_fp8_large_linears_sampled(acc, cfg, name):
                                              np.zeros((cs.stop - cs.start, lin.r)),
                                              S=np.zeros((rs.stop - rs.start, lin.r)), want_dW=False)[0]
     gu.check_outputs(have, want, 1e-2, name + ".fp8")
+
+
+def test_hot_path_and_its_fp8_form_replay_from_a_hip_graph(acc):
+    """Forward + backward + dense dW of the layer, in bf16 and on 8-bit operands, captured once and replayed: the
+    calls only enqueue kernels (no allocation, no memset, no synchronisation).  Each replay runs after eager work of
+    the program's own and must reproduce the eager results bit for bit."""
+    import torch
+    dev = "cuda:0"
+    lin = inputs.Linear("graph.hot", 2100, 1024, 1536, 64, seed=9)
+    data = inputs.make(lin)
+    bf = torch.bfloat16
+    X, W, dY = (acc.to_device(data[k], dev) for k in ("X", "W", "dY"))
+    x8, sx = _cast(data["X"], "e4m3"); w8, sw = _cast(data["W"], "e4m3"); dy8, sdy = _cast(data["dY"], "e5m2")
+    X8, W8, dY8 = (torch.from_numpy(a).to(dev) for a in (x8, w8, dy8))
+    desc = acc.make_desc(lin.n, lin.d_in, lin.d_out, lin.r, seed=lin.seed)
+    out = {k: torch.empty(s, dtype=bf, device=dev) for k, s in (
+        ("Y", (lin.n, lin.d_out)), ("dX", (lin.n, lin.d_in)), ("Xs", (lin.d_in, lin.r)), ("Gr", (lin.r, lin.d_out)),
+        ("dW", (lin.d_in, lin.d_out)), ("Y8", (lin.n, lin.d_out)), ("dX8", (lin.n, lin.d_in)),
+        ("Xs8", (lin.d_in, lin.r)), ("Gr8", (lin.r, lin.d_out)), ("dW8", (lin.d_in, lin.d_out)))}
+    ws_f, ws_b = acc.alloc_workspace(desc, False, dev), acc.alloc_workspace(desc, True, dev)
+
+    def enqueue():
+        acc.acc_linear_fwd(desc, X, W, out["Y"], out["Xs"], ws_f)
+        acc.acc_linear_bwd(desc, dY, W, out["Xs"], out["dX"], out["Gr"], out["dW"], ws_b)
+        acc.acc_linear_fwd_fp8(desc, X, X8, W8, sx * sw, out["Y8"], out["Xs8"], ws_f)
+        acc.acc_linear_bwd_fp8(desc, dY, dY8, acc.ACC_FP8_E5M2, W8, sdy * sw, out["Xs8"], out["dX8"], out["Gr8"],
+                               out["dW8"], ws_b)
+
+    enqueue()
+    torch.cuda.synchronize()
+    eager = {k: t.clone() for k, t in out.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in out.values():
+            t.fill_(3.0)
+        ws_f.fill_(0xAB); ws_b.fill_(0xCD)          # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, t in out.items():
+            assert torch.equal(t, eager[k]), (rep, k)
