@@ -41,9 +41,23 @@ __device__ __forceinline__ u32x2 lds_read_tr8_b64(const char* lds, int byte_off)
                                        (v2i __attribute__((address_space(3)))*)(uintptr_t)(uint32_t)(uintptr_t)(lds + byte_off)));
 }
 
-// buffer_to_lds_b128 with the vector offset formed inside the block, lane part + a scalar: the sum needs one
-// temporary register at the point of use and cannot be split up and kept per wave-load by the compiler.  The whole
-// byte offset is in the vector offset, so the resource's range check sees all of it.
+// A transfer as the slot program issues it, in two parts.  set_lds_dest writes M0 (the LDS destination) at the end
+// of the slot before; transfer_at_m0 is the transfer alone, right behind its slot's matrix instruction, which also
+// is the wait state the hardware asks for between a write of M0 and its use.  The vector offset is formed inside
+// the block, lane part + a scalar: the sum needs one temporary register at the point of use and cannot be split up
+// and kept per wave-load by the compiler; the whole byte offset is in the vector offset, so the resource's range
+// check sees all of it.
+__device__ __forceinline__ void set_lds_dest(uint32_t& m0_token, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %1" : "={m0}"(m0_token) : "s"(lds_wave_base));
+}
+__device__ __forceinline__ void transfer_at_m0(u32x4 rsrc, uint32_t voffset, uint32_t scalar_part, uint32_t m0_token) {
+  uint32_t sum;
+  asm volatile("v_add_u32 %0, %2, %1\n\tbuffer_load_dwordx4 %0, %3, 0 offen lds"
+               : "=&v"(sum)
+               : "v"(voffset), "s"(scalar_part), "s"(rsrc), "{m0}"(m0_token)
+               : "memory");
+}
+// Both parts in one block (prologue).
 __device__ __forceinline__ void buffer_to_lds_b128_sum(u32x4 rsrc, uint32_t voffset, uint32_t scalar_part,
                                                        uint32_t lds_wave_base) {
   uint32_t sum;
@@ -128,6 +142,15 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
     else
       buffer_to_lds_b128_sum(r.b_rsrc, b_voff[(g - A_LOADS) & 1], (uint32_t)kt * b_kstep + (g - A_LOADS) * b_tstep,
                              stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024);
+  };
+
+  uint32_t m0_token = 0;
+  auto lds_dest = [&](int g, uint32_t stage) -> uint32_t {
+    return g < A_LOADS ? stage + (g * NW + wave) * 1024 : stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024;
+  };
+  auto issue_at_m0 = [&](const TileRef& r, int g, int kt) {
+    if (g < A_LOADS) transfer_at_m0(r.a_rsrc, a_voff, (uint32_t)kt * BK + g * a_tstep, m0_token);
+    else transfer_at_m0(r.b_rsrc, b_voff[(g - A_LOADS) & 1], (uint32_t)kt * b_kstep + (g - A_LOADS) * b_tstep, m0_token);
   };
 
   // ---- LDS read offsets of the operands ----
@@ -259,7 +282,7 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
         acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], 0, A_FMT, 0, 0, 0, 0);
       }
       if (q >= DMA_Q && (q - DMA_Q) % DMA_EVERY == 0 && (q - DMA_Q) / DMA_EVERY < NG)
-        issue_one(ref2, (q - DMA_Q) / DMA_EVERY, k2, cur_lds);
+        issue_at_m0(ref2, (q - DMA_Q) / DMA_EVERY, k2);
       if (h == 0) {
         // B operands 4 .. 7 of this K tile (slots 2, 8, 14, 20)
         if (q >= 2 && (q - 2) % 6 == 0 && (q - 2) / 6 < 4) b[4 + (q - 2) / 6] = read_b(cur, 4 + (q - 2) / 6);
@@ -276,6 +299,8 @@ __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, in
           if (i >= 2 && (jj & 1) == 1) { store_back(i - 2, jj - 1, back[0]); store_back(i - 2, jj, back[1]); }
         }
       }
+      if (q + 1 >= DMA_Q && (q + 1 - DMA_Q) % DMA_EVERY == 0 && (q + 1 - DMA_Q) / DMA_EVERY < NG)
+        set_lds_dest(m0_token, lds_dest((q + 1 - DMA_Q) / DMA_EVERY, cur_lds));
       __builtin_amdgcn_sched_barrier(0);
     });
     if constexpr (FINAL) {
