@@ -137,9 +137,9 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
   // matrix instruction is the wait state the hardware asks for between a write of M0 and its use).  Against the
   // one-piece form (M0 write, s_nop, transfer in one slot): 0.5458 against 0.5502 ms per step, three same-box pairs.
   uint32_t m0_token = 0;
-  auto set_m0 = [&](int g, uint32_t stage) {
-    const uint32_t dest = g < A_LOADS ? stage + (g * NW + wave) * 1024 : stage + A_BYTES + ((g - A_LOADS) * NW + wave) * 1024;
-    asm volatile("s_mov_b32 m0, %1" : "={m0}"(m0_token) : "s"(dest));
+  auto set_m0 = [&](int g, uint32_t stage_wave) {  // stage_wave: the stage's LDS address + wave * 1024
+    const int part = g < A_LOADS ? g * NW * 1024 : A_BYTES + (g - A_LOADS) * NW * 1024;  // a constant per wave-load
+    asm volatile("s_add_u32 m0, %1, %2" : "={m0}"(m0_token) : "s"(stage_wave), "s"(part) : "scc");
   };
   auto issue_at_m0 = [&](const TileRef& r, int g, int kt) {
     if (g < A_LOADS)
@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       if (j == 0 && i >= 1) a[i - 1] = read_a(cur, 1, i - 1);
       if (j == 4) b1[i] = read_b(cur, 1, i);
       if (CARRY && q < 16) carry_slot(q);
-      if (q >= 1 && (q - 1) % S0 == 0 && (q - 1) / S0 < NG - N1) set_m0(N1 + (q - 1) / S0, nxt_lds);
+      if (q >= 1 && (q - 1) % S0 == 0 && (q - 1) / S0 < NG - N1) set_m0(N1 + (q - 1) / S0, nxt_lds + wave * 1024);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
         if (i >= 2 && j >= 4) store_back(i - 2, j - 4, back[j - 4]);
       }
       if (q >= BAR_Q + 1 && (q - BAR_Q - 1) % S1 == 0 && (q - BAR_Q - 1) / S1 < N1)
-        set_m0((q - BAR_Q - 1) / S1, cur_lds);
+        set_m0((q - BAR_Q - 1) / S1, cur_lds + wave * 1024);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
