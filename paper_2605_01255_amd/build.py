@@ -35,6 +35,37 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def kernel_resources() -> dict:
+    """Compile the device code only and return {mangled kernel name: {"scratch": bytes per lane, "vgpr_spill": n}}
+    from the compiler's resource remarks.  The slot-program kernels keep whole arrays in registers; a build that
+    puts them into scratch memory computes the same results many times slower, so this is worth checking."""
+    import re
+    import tempfile
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    out = {}
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [hipcc, *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage", *sources(),
+               "-o", os.path.join(tmp, "dev.o")]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stderr)
+        name = None
+        for line in res.stderr.splitlines():
+            m = re.search(r"remark: Function Name: (\S+)", line)
+            if m:
+                name = m.group(1)
+                out[name] = {}
+                continue
+            m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
+            if m and name:
+                out[name]["scratch"] = int(m.group(1))
+            m = re.search(r"remark:\s+VGPRs Spill: (\d+)", line)
+            if m and name:
+                out[name]["vgpr_spill"] = int(m.group(1))
+    return out
+
+
 def build_c_client(verbose: bool = True) -> str:
     """The plain-C client of the ABI under tests/c_client (host code only: gcc-style compile through hipcc,
     linked against the HIP runtime and libacc.so, found at run time next to this package)."""
