@@ -194,3 +194,58 @@ def test_hot_path_and_its_fp8_form_replay_from_a_hip_graph(acc):
         torch.cuda.synchronize()
         for k, t in out.items():
             assert torch.equal(t, eager[k]), (rep, k)
+
+
+def _fp8_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        n = int(rng.integers(1, 40)) * 97 + int(rng.integers(1, 97))          # ragged token counts, 98 .. 3900
+        d_in = 128 * int(rng.integers(3, 13))
+        d_out = 128 * int(rng.integers(3, 13))
+        out.append((n, d_in, d_out, int(rng.choice([16, 64])), int(rng.integers(0, 3)) * 16,
+                    int(rng.integers(0, 3)) * 16, int(rng.integers(0, 3)) * 16))
+    return out
+
+
+@pytest.mark.parametrize("n,d_in,d_out,r,pad_x,pad_w,pad_y", _fp8_shapes(6, 77))
+def test_fp8_seeded_random_shapes_with_row_strides(acc, n, d_in, d_out, r, pad_x, pad_w, pad_y):
+    """Seeded random sizes (ragged token counts, every multiple of 128 from 384 to 1536 as contraction length) with
+    row strides wider than the rows (multiples of 16 bytes for the 8-bit operands): exact products against the
+    oracle, padding columns untouched, in both weight orientations."""
+    import torch
+    dev = "cuda:0"
+    lin = inputs.Linear(f"fp8_rand_{n}_{d_in}_{d_out}", n, d_in, d_out, r, seed=3)
+    data = inputs.make(lin)
+    x8, sx = _cast(data["X"], "e4m3"); w8, sw = _cast(data["W"], "e4m3"); dy8, sdy = _cast(data["dY"], "e5m2")
+    Xq, Wq = inputs.fp8_bits_to_f64(x8, "e4m3") * sx, inputs.fp8_bits_to_f64(w8, "e4m3") * sw
+    dYq = inputs.fp8_bits_to_f64(dy8, "e5m2") * sdy
+    want = {"Y": orc.linear_fwd(Xq, Wq, S=np.zeros((n, r)))[0],
+            "dX": orc.linear_bwd(dYq, Wq, np.zeros((d_in, r)), S=np.zeros((n, r)), want_dW=False)[0]}
+    for w_out_in in (False, True):
+        print(f"fp8 random case n={n} {d_in}->{d_out} pads={pad_x},{pad_w},{pad_y} w_out_in={w_out_in}", flush=True)
+        w_host = np.ascontiguousarray(w8.T) if w_out_in else w8
+        ldx, ldw, ldy = d_in + pad_x, w_host.shape[1] + pad_w, d_out + pad_y
+
+        def padded(a, ld, fill):
+            buf = torch.full((a.shape[0], ld), fill, dtype=a.dtype, device=dev)
+            buf[:, :a.shape[1]] = a
+            return buf
+        X = padded(acc.to_device(data["X"], dev), ldx, float("nan"))
+        dY = padded(acc.to_device(data["dY"], dev), ldy, float("nan"))
+        X8 = padded(torch.from_numpy(x8).to(dev), ldx, 0x7F)       # the padding holds the format's NaN pattern
+        dY8 = padded(torch.from_numpy(dy8).to(dev), ldy, 0x7F)
+        W8 = padded(torch.from_numpy(w_host).to(dev), ldw, 0x7F)
+        desc = acc.make_desc(n, d_in, d_out, r, seed=lin.seed, ldx=ldx, ldw=ldw, ldy=ldy,
+                             flags=acc.ACC_FLAG_W_OUT_IN if w_out_in else 0)
+        Y = torch.full((n, ldy), 7.0, dtype=torch.bfloat16, device=dev)
+        dX = torch.full((n, ldx), 7.0, dtype=torch.bfloat16, device=dev)
+        Xs = torch.empty(d_in, r, dtype=torch.bfloat16, device=dev)
+        Gr = torch.empty((d_out, r) if w_out_in else (r, d_out), dtype=torch.bfloat16, device=dev)
+        acc.acc_linear_fwd_fp8(desc, X, X8, W8, sx * sw, Y, Xs, acc.alloc_workspace(desc, False, dev))
+        acc.acc_linear_bwd_fp8(desc, dY, dY8, acc.ACC_FP8_E5M2, W8, sdy * sw, None, dX, Gr, None,
+                               acc.alloc_workspace(desc, True, dev))
+        torch.cuda.synchronize()
+        Yh, dXh = acc.to_host_f64(Y), acc.to_host_f64(dX)
+        assert np.all(Yh[:, d_out:] == 7.0) and np.all(dXh[:, d_in:] == 7.0)
+        gu.check_outputs({"Y": Yh[:, :d_out], "dX": dXh[:, :d_in]}, want, 1e-2, lin.name)
