@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/acc.h"
 
 namespace acc {
@@ -22,6 +24,17 @@ __device__ __forceinline__ float to_f32(bf16 v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16 from_f32<bf16>(float v) { return (bf16)v; }  // RNE (v_cvt_pk_bf16_f32)
+
+// Compile-time loop: f(integral_constant<int, B>) ... f(integral_constant<int, E - 1>).  The slot programs of the GEMM
+// kernels index their register arrays with the slot number; with an ordinary loop the compiler has to unroll it before it can
+// keep those arrays in registers, and when it does that too late they end up in scratch memory (same results,
+// thirty times slower).
+template <int B, int E, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    static_for<B + 1, E>(f);
+  }
+}
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }

@@ -34,12 +34,11 @@
 // barrier 67; the matrix instructions alone need 2048 back to back, about 2380 at the rate one wave issues them, and
 // the rest is the issue of the sixteen 1 KB transfers per wave (a wave issues in order).  Two waves per SIMD (eight
 // waves of 128 x 64) hide that but read 1.5 x the operand bytes from LDS: equal in time.
-// A warning about builds, not about the hardware: the slot loops index the register arrays (acc, a, b0, b1) with the
-// slot number, so the arrays stay in registers only if the compiler unrolls those loops before it decides where
-// arrays live.  Two earlier variants of this kernel (denser wave-loads; four wave-loads sharing one LDS base in M0
-// through the instruction's immediate offset) came out with the arrays in scratch memory: same results, thirty
-// times slower.  After any change check that the kernel's scratch size is still zero
-// (-Rpass-analysis=kernel-resource-usage); acc_gemm8.h avoids the question with a compile-time loop.
+// A warning about builds, not about the hardware: the slot program indexes the register arrays (acc, a, b0, b1) with
+// the slot number, so it is written as a compile-time loop (static_for).  As ordinary loops under #pragma unroll, two
+// earlier variants of this kernel (denser wave-loads; four wave-loads sharing one LDS base in M0 through the
+// instruction's immediate offset) came out with the arrays in scratch memory, the compiler having unrolled too late:
+// same results, thirty times slower.  tests/test_kernel_resources.py checks that the scratch size stays zero.
 #pragma once
 #include <type_traits>
 
@@ -249,9 +248,9 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
     const char* nxt = smem + (sc ^ 1) * STAGE;
     const uint32_t cur_lds = smem_lds + sc * STAGE, nxt_lds = smem_lds + (sc ^ 1) * STAGE;
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int q = 0; q < 64; ++q) {  // k-step 0
-      const int i = q >> 3, j = q & 7;
+    static_for<0, 64>([&](auto slot) {  // k-step 0
+      constexpr int q = decltype(slot)::value;
+      constexpr int i = q >> 3, j = q & 7;
       if (q == 0) a[7] = read_a(cur, 0, 7);
       if constexpr (ZERO) {
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
@@ -265,10 +264,10 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       if (CARRY && q < 16) carry_slot(q);
       if (q >= 1 && (q - 1) % S0 == 0 && (q - 1) / S0 < NG - N1) set_m0(N1 + (q - 1) / S0, nxt_lds + wave * 1024);
       __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int q = 0; q < 64; ++q) {  // k-step 1
-      const int i = q >> 3, j = q & 7;
+    });
+    static_for<0, 64>([&](auto slot) {  // k-step 1
+      constexpr int q = decltype(slot)::value;
+      constexpr int i = q >> 3, j = q & 7;
       if (q == 0) a[7] = read_a(cur, 1, 7);
       if (q == BAR_Q) {
         wait_vmcnt0();
@@ -279,9 +278,10 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       if (q >= BAR_Q + 2 && (q - BAR_Q - 2) % S1 == 0 && (q - BAR_Q - 2) / S1 < N1)
         issue_at_m0(ref2, (q - BAR_Q - 2) / S1, k2);
       // operands of the next K tile's k-step 0: A operand i once block row i is done and the barrier is passed
-#pragma unroll
-      for (int e = 0; e < AEARLY; ++e)
+      static_for<0, AEARLY>([&](auto early) {
+        constexpr int e = decltype(early)::value;
         if (q == BAR_Q + 4 * e) a[e] = read_a(nxt, 0, e);
+      });
       if (j == 0 && i >= AEARLY + 1) a[i - 1] = read_a(nxt, 0, i - 1);
       {
         constexpr int SP = (63 - BAR_Q - 1) / 8;  // B operands of the next K tile, spread over the rest of the k-step
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       if (q >= BAR_Q + 1 && (q - BAR_Q - 1) % S1 == 0 && (q - BAR_Q - 1) / S1 < N1)
         set_m0((q - BAR_Q - 1) / S1, cur_lds + wave * 1024);
       __builtin_amdgcn_sched_barrier(0);
-    }
+    });
   };
 
   // ---- prologue of the work-group's first tile ----

@@ -67,17 +67,6 @@ __device__ __forceinline__ void buffer_to_lds_b128_sum(u32x4 rsrc, uint32_t voff
                : "memory");
 }
 
-// Compile-time loop: f(integral_constant<int, B>) ... f(integral_constant<int, E - 1>).  The slot program indexes
-// its register arrays with the slot number; with an ordinary loop the compiler has to unroll it before it can
-// keep those arrays in registers, and when it does that too late they end up in scratch memory (same results,
-// thirty times slower).
-template <int B, int E, typename F> __device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(std::integral_constant<int, B>{});
-    static_for<B + 1, E>(f);
-  }
-}
-
 // A_FMT: 0 = fp8 (e4m3), 1 = bf8 (e5m2) for the A operand; B is always fp8 (e4m3).
 template <bool B_KMAJOR, int A_FMT>
 __global__ __launch_bounds__(256) void gemm8_persist_kernel(FastGemmParams p, int n_slots) {
