@@ -27,7 +27,9 @@
 // Measured on the 3B-shaped projection (a step of the layer, same-box pairs): barrier before slot 72 0.547 - 0.552
 // ms against 0.553 - 0.557 before slot 80; before slot 88 0.545 - 0.546 against 0.541 - 0.542 before slot 80; all
 // sixteen wave-loads after the barrier, one every three slots, 0.565 against 0.553 - 0.557; eight after it and
-// eight in the next k-step 0: equal; one wave-load every second slot: 0.561 against 0.550.  Spreading the wave-loads evenly (nine after the barrier, one every six
+// eight in the next k-step 0: equal; one wave-load every second slot: 0.561 against 0.550.  With M0 written a slot
+// ahead (below) the same comparison again: sixteen after the barrier every three slots 0.574, fourteen every three
+// 0.570, ten after it and six before 0.5588, eight and eight every six slots 0.5695 against 0.5585.  Spreading the wave-loads evenly (nine after the barrier, one every six
 // slots, seven in the next k-step 0, one every six) 0.5545 against 0.5507; the last of them 14 slots before the
 // barrier instead of 58: 0.584 (the transfers need their thousand clocks to land).
 // What is left inside a K tile (in-kernel timestamps): 2924 clocks, of which the wait for the transfers is 8 and the
