@@ -36,17 +36,21 @@ def build(verbose: bool = True, extra_flags=()) -> str:
 
 
 def kernel_resources() -> dict:
-    """Compile the device code only and return {mangled kernel name: {"scratch": bytes per lane, "vgpr_spill": n}}
-    from the compiler's resource remarks.  The slot-program kernels keep whole arrays in registers; a build that
-    puts them into scratch memory computes the same results many times slower, so this is worth checking."""
+    """Compile the device code only and return, per mangled kernel name, {"scratch": bytes per lane, "vgpr_spill": n}
+    from the compiler's resource remarks and {"mfma_regions": {k: number of scheduling regions that hold k matrix
+    instructions}} from the assembly (a region = the instructions between two scheduling fences; kernels without
+    fences have none).  The slot-program kernels keep whole arrays in registers and place one matrix instruction
+    per slot: a build that puts the arrays into scratch memory, or that moves the matrix instructions out of their
+    slots, computes the same results much more slowly, so both are worth checking."""
     import re
     import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
     out = {}
     with tempfile.TemporaryDirectory() as tmp:
-        cmd = [hipcc, *flags, "--cuda-device-only", "-c", "-Rpass-analysis=kernel-resource-usage", *sources(),
-               "-o", os.path.join(tmp, "dev.o")]
+        asm_path = os.path.join(tmp, "dev.s")
+        cmd = [hipcc, *flags, "--cuda-device-only", "-S", "-Rpass-analysis=kernel-resource-usage", *sources(),
+               "-o", asm_path]
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed:\n" + res.stderr)
@@ -63,6 +67,22 @@ def kernel_resources() -> dict:
             m = re.search(r"remark:\s+VGPRs Spill: (\d+)", line)
             if m and name:
                 out[name]["vgpr_spill"] = int(m.group(1))
+        name, count, regions = None, 0, {}
+        with open(asm_path) as f:
+            for line in f:
+                m = re.match(r"(\w+):\s", line)
+                if m and m.group(1) in out:
+                    name, count, regions = m.group(1), 0, {}
+                elif name is None:
+                    continue
+                elif "v_mfma" in line:
+                    count += 1
+                elif "; sched_barrier" in line:
+                    regions[count] = regions.get(count, 0) + 1
+                    count = 0
+                elif "s_endpgm" in line:
+                    out[name]["mfma_regions"] = regions
+                    name = None
     return out
 
 

@@ -64,9 +64,11 @@ __device__ __forceinline__ int swz_n16(int krow) { return ((krow & 3) << 2) | ((
 //   * In the last K tile block row i (16 x 128 outputs per wave) is final after slot 64 + 8 i + 7.  Its read-out
 //     is 16 micro-operations: eight staging writes (convert to bf16, 8 bytes per lane, into one of two private
 //     4 KB regions per wave, 16-byte chunk index XOR row) in the slots of block row i + 1, four 16-byte read-backs
-//     and four 16-byte global stores (whole 256-byte rows) in the slots of block row i + 2.  Rows 6 and 7 finish
-//     in the first sixteen slots of the next output tile's first k-step, before that k-step restarts their
-//     accumulators (slots 48 and 56).
+//     and four 16-byte global stores (whole 256-byte rows) in the slots of block row i + 2.  Block row 7 is staged
+//     behind the last matrix instruction, so no accumulator lives on into the next output tile; the read-backs and
+//     stores of rows 6 and 7 ride in the first sixteen slots of the next output tile's first k-step.  (With row 7
+//     staged in those slots instead the kernel measured the same, 0.5472 against 0.5509 ms per step; the compiler
+//     then keeps two register assignments of the accumulators and 130 copies between them.)
 // LDS: two 64 KB stages + 32 KB of staging regions = 160 KB.  Restrictions (host): bf16 output, no accumulation
 // into C, no K split, K >= 192.
 template <bool B_KMAJOR, int N1 = 12, int S1 = 4, int S0 = 4>
@@ -201,8 +203,8 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   };
-  __amdgpu_buffer_rsrc_t c_rs;
-  uint32_t c_voff;
+  __amdgpu_buffer_rsrc_t c_rs = __builtin_amdgcn_make_buffer_rsrc((void*)C, 0, 0, 0x00020000);  // empty: nothing to store yet
+  uint32_t c_voff = 0xFFFFFFF0u;
   auto set_output = [&](const TileRef& t) {
     const int64_t gm_base = t.m0 + wm * TB * 16, gn_base = t.n0 + wn * TB * 16;
     int64_t c_rows = p.M - gm_base;
@@ -229,18 +231,24 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
     __builtin_amdgcn_raw_buffer_store_b128(v, c_rs, c_voff, soff, 0);
   };
   u32x4 back[4];
-  // what is left of the previous output tile's read-out (block rows 6 and 7), as work for slots 0 .. 15
+  // What is left of the previous output tile's read-out, as work for slots 0 .. 15 of the next K tile: block rows 6
+  // and 7 sit in the two staging regions when an output tile's last K tile ends (row 7 is staged behind that K
+  // tile's last matrix instruction, so no accumulator lives on into the next output tile and the compiler keeps
+  // one register assignment for all of them); their read-backs and global stores follow here.
   auto carry_slot = [&](int q) {
     if (q == 0) wave_fence();
-    if (q < 8) stage_write(7, q);
     if (q < 4) back[q] = read_back(6, q);
     else if (q < 8) store_back(6, q - 4, back[q - 4]);
-    if (q == 8) wave_fence();
-    if (q >= 8 && q < 12) back[q - 8] = read_back(7, q - 8);
-    if (q >= 12) store_back(7, q - 12, back[q - 12]);
+    else if (q < 12) back[q - 8] = read_back(7, q - 8);
+    else store_back(7, q - 12, back[q - 12]);
   };
 
   bf16x8 a[TB], b0[TB], b1[TB];
+  // A matrix instruction has no side effect, so nothing but heuristics keeps it in the slot it is written in (one
+  // build of this kernel had the 72 of a K tile's first slots behind the barrier, all transfers and LDS reads of
+  // those slots running with the matrix pipe idle: 15 % slower).  The empty statement below makes the result a value
+  // the compiler must have at this point of the program order; it emits nothing.
+  auto pin = [](f32x4& v) { asm volatile("" : "+a"(v)); };
 
   // One K tile (see the slot program at the top of this file).  sc: its stage.  ref1 / k1: the K tile that follows
   // (its wave-loads 12 .. 15 go out here), ref2 / k2: the one after that (wave-loads 0 .. 11).
@@ -260,6 +268,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
       } else {
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0[j], a[i], acc[i][j], 0, 0, 0);
       }
+      pin(acc[i][j]);
       if (q >= 2 && (q - 2) % S0 == 0 && (q - 2) / S0 < NG - N1) issue_at_m0(ref1, N1 + (q - 2) / S0, k1);
       if (j == 0 && i >= 1) a[i - 1] = read_a(cur, 1, i - 1);
       if (j == 4) b1[i] = read_b(cur, 1, i);
@@ -277,6 +286,7 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
         __builtin_amdgcn_sched_barrier(0);
       }
       acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1[j], a[i], acc[i][j], 0, 0, 0);
+      pin(acc[i][j]);
       if (q >= BAR_Q + 2 && (q - BAR_Q - 2) % S1 == 0 && (q - BAR_Q - 2) / S1 < N1)
         issue_at_m0(ref2, (q - BAR_Q - 2) / S1, k2);
       // operands of the next K tile's k-step 0: A operand i once block row i is done and the barrier is passed
@@ -300,6 +310,9 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
         set_m0((q - BAR_Q - 1) / S1, cur_lds + wave * 1024);
       __builtin_amdgcn_sched_barrier(0);
     });
+    if constexpr (FINAL) {
+      static_for<0, TB>([&](auto col) { stage_write(TB - 1, decltype(col)::value); });
+    }
   };
 
   // ---- prologue of the work-group's first tile ----
@@ -340,13 +353,15 @@ __global__ __launch_bounds__(256) void gemm16_persist_kernel(FastGemmParams p, i
     const int next_idx = next_slot(idx);
     const bool has_next = next_idx < n_slots;
     const TileRef next_t = has_next ? tile_ref(next_idx) : cur_t;
-    // K tile 0: multiplies onto zero and, after the first output tile, finishes the previous read-out
-    if (idx == first_idx) ktile(par, cur_t, 1, cur_t, 2, T{}, F{}, F{});
-    else ktile(par, cur_t, 1, cur_t, 2, T{}, T{}, F{});
-    int kt = 1;
-    for (; kt + 2 < KT; ++kt) ktile((kt + par) & 1, cur_t, kt + 1, cur_t, kt + 2, F{}, F{}, F{});
-    ktile((kt + par) & 1, cur_t, kt + 1, next_t, 0, F{}, F{}, F{});  // last but one
-    ++kt;
+    // K tile 0: multiplies onto zero and finishes the previous read-out (before the first output tile the staging
+    // regions hold nothing and the output resource is empty, so those stores are dropped)
+    ktile(par, cur_t, 1, cur_t, 2, T{}, T{}, F{});
+    // K tiles 1 .. KT - 2; the last of them already fetches the next output tile's first K tile
+    for (int kt = 1; kt + 1 < KT; ++kt) {
+      const bool wraps = kt + 2 >= KT;
+      ktile((kt + par) & 1, cur_t, kt + 1, wraps ? next_t : cur_t, wraps ? 0 : kt + 2, F{}, F{}, F{});
+    }
+    const int kt = KT - 1;
     set_output(cur_t);
     ktile((kt + par) & 1, next_t, 0, next_t, 1, F{}, F{}, T{});       // last: the read-out starts
     if (!has_next) break;
