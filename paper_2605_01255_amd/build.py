@@ -35,13 +35,62 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return LIB
 
 
+def _scalar_regs(token: str) -> set:
+    """Scalar registers an assembly operand names: s7, s[4:7], vcc_lo, vcc, m0."""
+    import re
+    token = token.strip(",")
+    m = re.fullmatch(r"s\[(\d+):(\d+)\]", token)
+    if m:
+        return {f"s{k}" for k in range(int(m.group(1)), int(m.group(2)) + 1)}
+    if token == "vcc":
+        return {"vcc_lo", "vcc_hi"}
+    return {token} if re.fullmatch(r"s\d+|vcc_lo|vcc_hi|m0", token) else set()
+
+
+def scan_assembly(lines, names) -> dict:
+    """{kernel: {"mfma_regions": ..., "stale_transfer_operands": ...}} for the kernels in `names`, from the lines of
+    the compiler's assembly output (see kernel_resources)."""
+    import re
+    found = {}
+    name, count, regions, recent, stale = None, 0, {}, [], 0
+    for line in lines:
+        m = re.match(r"(\w+):\s", line)
+        if m and m.group(1) in names:
+            name, count, regions, recent, stale = m.group(1), 0, {}, [], 0
+            continue
+        if name is None:
+            continue
+        text = line.strip()
+        if "; sched_barrier" in text:
+            regions[count] = regions.get(count, 0) + 1
+            count = 0
+        if not text or text[0] in ";." or text.endswith(":"):
+            continue
+        if "v_mfma" in text:
+            count += 1
+        if text.startswith("buffer_load") and text.endswith(" lds"):
+            used = set().union(*(_scalar_regs(t) for t in text.split()[1:]))
+            stale += sum(1 for w in recent[-5:] if w & used)
+        w = re.match(r"v_read(?:first)?lane_b32 (\S+),", text)
+        recent.append(_scalar_regs(w.group(1)) if w else set())
+        if "s_endpgm" in text:
+            found[name] = {"mfma_regions": regions, "stale_transfer_operands": stale}
+            name = None
+    return found
+
+
 def kernel_resources() -> dict:
     """Compile the device code only and return, per mangled kernel name, {"scratch": bytes per lane, "vgpr_spill": n}
     from the compiler's resource remarks and {"mfma_regions": {k: number of scheduling regions that hold k matrix
     instructions}} from the assembly (a region = the instructions between two scheduling fences; kernels without
-    fences have none).  The slot-program kernels keep whole arrays in registers and place one matrix instruction
-    per slot: a build that puts the arrays into scratch memory, or that moves the matrix instructions out of their
-    slots, computes the same results much more slowly, so both are worth checking."""
+    fences have none) and {"stale_transfer_operands": n}.  The slot-program kernels keep whole arrays in registers and
+    place one matrix instruction per slot: a build that puts the arrays into scratch memory, or that moves the matrix
+    instructions out of their slots, computes the same results much more slowly, so both are worth checking.
+    stale_transfer_operands counts global -> LDS transfers (written as inline assembly, so the compiler does not
+    know them as memory instructions and inserts no wait states for them) that read a scalar register which one of
+    the five instructions before wrote from a vector register (v_readlane / v_readfirstlane: how the compiler
+    restores scalar registers it had parked in vector lanes): the hardware needs five wait states there, and without
+    them the transfer uses the register's old value."""
     import re
     import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -67,22 +116,9 @@ def kernel_resources() -> dict:
             m = re.search(r"remark:\s+VGPRs Spill: (\d+)", line)
             if m and name:
                 out[name]["vgpr_spill"] = int(m.group(1))
-        name, count, regions = None, 0, {}
         with open(asm_path) as f:
-            for line in f:
-                m = re.match(r"(\w+):\s", line)
-                if m and m.group(1) in out:
-                    name, count, regions = m.group(1), 0, {}
-                elif name is None:
-                    continue
-                elif "v_mfma" in line:
-                    count += 1
-                elif "; sched_barrier" in line:
-                    regions[count] = regions.get(count, 0) + 1
-                    count = 0
-                elif "s_endpgm" in line:
-                    out[name]["mfma_regions"] = regions
-                    name = None
+            for name, found in scan_assembly(f, set(out)).items():
+                out[name].update(found)
     return out
 
 
